@@ -1,0 +1,135 @@
+"""CPU oracle for causal linear attention with per-head decay (fp64, NumPy).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+GPU library must compute.  It shares no code with the HIP path, is never
+imported by it, and is only used by the tests, the smoke check and the CPU
+baseline leg of the benchmark.
+
+Two independent forms of the same exact result are given, per (batch, head):
+
+  form (i)  "left product" (Alg. 1, Eq. 3 of Sec. 3.1, with the decay mask of
+            App. A, first equation block):
+                A[t, s] = lambda^(t-s) if t >= s else 0          (diagonal = 1)
+                P = (Q K^T) * A ,   O = P V
+            and its gradients, with G = (dO V^T) * A:
+                dQ = G K ,  dK = G^T Q ,  dV = P^T dO
+            (the n-row statement of the intra-block lines of Alg. 6).
+
+  form (ii) "right product" recurrence (Alg. 2; with decay: App. A second
+            equation block and App. C "Forward Pass"/"Backward Pass"):
+                kv_0 = 0,  kv_t = lambda kv_{t-1} + k_t v_t^T,  o_t^T = q_t^T kv_t
+                dq_t^T = do_t^T kv_t^T
+                dkv_{n+1} = 0,  dkv_t = lambda dkv_{t+1} + q_t do_t^T
+                dk_t^T = v_t^T dkv_t^T ,  dv_t^T = k_t^T dkv_t
+            kv_t and dkv_t are d x d with rows = key feature, cols = value
+            feature.  dkv_t includes the term of position t itself.
+
+Readings taken where the paper's text is inconsistent:
+  * the mask diagonal is included (a token attends to itself), as Alg. 1 and
+    Alg. 5 state and as o_t = q_t^T kv_t with kv_t containing k_t v_t^T implies;
+  * outer products are always k v^T (d x d), whatever row/column notation a
+    given line of the appendix uses;
+  * lambda is a constant: no gradient flows to it (Sec. 4.1 keeps it fixed);
+  * no 1/sqrt(d) scaling and no normalisation are applied (Sec. 3.1).
+
+All arithmetic is fp64.  Tensors are [B, H, n, d]; `lam` has H entries.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def _as64(x):
+    return np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+
+
+def decay_matrix(n: int, lam: float) -> np.ndarray:
+    """A[t, s] = lam^(t-s) for t >= s, else 0 (n x n, fp64)."""
+    t = np.arange(n)[:, None]
+    s = np.arange(n)[None, :]
+    diff = t - s
+    A = np.zeros((n, n), dtype=np.float64)
+    mask = diff >= 0
+    A[mask] = np.power(float(lam), diff[mask].astype(np.float64))
+    return A
+
+
+# --------------------------------------------------------------------------
+# form (i): quadratic masked form
+# --------------------------------------------------------------------------
+def left_product_fwd(Q, K, V, lam):
+    Q, K, V = _as64(Q), _as64(K), _as64(V)
+    B, H, n, d = Q.shape
+    O = np.empty_like(Q)
+    for h in range(H):
+        A = decay_matrix(n, lam[h])
+        for b in range(B):
+            P = (Q[b, h] @ K[b, h].T) * A
+            O[b, h] = P @ V[b, h]
+    return O
+
+
+def left_product_bwd(Q, K, V, lam, dO):
+    Q, K, V, dO = _as64(Q), _as64(K), _as64(V), _as64(dO)
+    B, H, n, d = Q.shape
+    dQ = np.empty_like(Q)
+    dK = np.empty_like(Q)
+    dV = np.empty_like(Q)
+    for h in range(H):
+        A = decay_matrix(n, lam[h])
+        for b in range(B):
+            P = (Q[b, h] @ K[b, h].T) * A
+            G = (dO[b, h] @ V[b, h].T) * A
+            dQ[b, h] = G @ K[b, h]
+            dK[b, h] = G.T @ Q[b, h]
+            dV[b, h] = P.T @ dO[b, h]
+    return dQ, dK, dV
+
+
+# --------------------------------------------------------------------------
+# form (ii): token-by-token recurrence
+# --------------------------------------------------------------------------
+def recurrence_fwd(Q, K, V, lam):
+    Q, K, V = _as64(Q), _as64(K), _as64(V)
+    B, H, n, d = Q.shape
+    O = np.empty_like(Q)
+    for b in range(B):
+        for h in range(H):
+            l = float(lam[h])
+            kv = np.zeros((d, d), dtype=np.float64)
+            for t in range(n):
+                kv = l * kv + np.outer(K[b, h, t], V[b, h, t])
+                O[b, h, t] = Q[b, h, t] @ kv
+    return O
+
+
+def recurrence_bwd(Q, K, V, lam, dO):
+    Q, K, V, dO = _as64(Q), _as64(K), _as64(V), _as64(dO)
+    B, H, n, d = Q.shape
+    dQ = np.empty_like(Q)
+    dK = np.empty_like(Q)
+    dV = np.empty_like(Q)
+    for b in range(B):
+        for h in range(H):
+            l = float(lam[h])
+            kv = np.zeros((d, d), dtype=np.float64)
+            for t in range(n):
+                kv = l * kv + np.outer(K[b, h, t], V[b, h, t])
+                dQ[b, h, t] = kv @ dO[b, h, t]
+            dkv = np.zeros((d, d), dtype=np.float64)
+            for t in range(n - 1, -1, -1):
+                dkv = l * dkv + np.outer(Q[b, h, t], dO[b, h, t])
+                dK[b, h, t] = dkv @ V[b, h, t]
+                dV[b, h, t] = K[b, h, t] @ dkv
+    return dQ, dK, dV
+
+
+def rel_max_err(x, ref) -> float:
+    """max|x - ref| / max|ref| over the whole tensor (the error measure the
+    parity tolerances are stated in)."""
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    denom = float(np.max(np.abs(ref)))
+    if denom == 0.0:
+        return float(np.max(np.abs(x)))
+    return float(np.max(np.abs(x - ref)) / denom)

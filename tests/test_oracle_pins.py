@@ -1,0 +1,258 @@
+"""Pins for the CPU oracle: it is checked against things other than itself.
+
+The paper prints no numeric worked example, so the pins are: hand-worked tiny
+cases (tests/golden), closed forms, textbook special cases, the agreement of
+the two independent forms (App. A proves them equal), finite differences,
+a blocked re-statement of Alg. 5/6 (App. C proves block form == token form),
+the trilinearity invariant and causality.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from conftest import load_golden
+
+LAMS = [1.0, 0.99, 0.5, 0.1]
+
+
+def _rand(B, H, n, d, seed):
+    rng = np.random.default_rng(seed)
+    return [rng.standard_normal((B, H, n, d)) for _ in range(4)]
+
+
+FWD_IMPLS = {
+    "left": oracle.left_product_fwd,
+    "rec": oracle.recurrence_fwd,
+    "c_rec": oracle.c_recurrence_fwd,
+}
+BWD_IMPLS = {
+    "left": oracle.left_product_bwd,
+    "rec": oracle.recurrence_bwd,
+    "c_rec": oracle.c_recurrence_bwd,
+}
+
+
+# ---- 1. hand-worked examples ------------------------------------------------
+@pytest.mark.parametrize("fixture", ["worked_example_a.txt", "worked_example_b.txt"])
+@pytest.mark.parametrize("impl", list(FWD_IMPLS))
+def test_worked_examples(fixture, impl):
+    g = load_golden(fixture)
+    lam = [g["lambda"]]
+    O = FWD_IMPLS[impl](g["Q"], g["K"], g["V"], lam)
+    dQ, dK, dV = BWD_IMPLS[impl](g["Q"], g["K"], g["V"], lam, g["dO"])
+    np.testing.assert_allclose(O, g["O"], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(dQ, g["dQ"], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(dK, g["dK"], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(dV, g["dV"], rtol=0, atol=1e-13)
+
+
+# ---- 2. the two forms agree (App. A induction) -------------------------------
+@pytest.mark.parametrize("n,d", [(1, 3), (5, 2), (17, 8), (64, 8)])
+def test_forms_agree(n, d):
+    Q, K, V, dO = _rand(2, len(LAMS), n, d, seed=n * 100 + d)
+    ref_o = oracle.left_product_fwd(Q, K, V, LAMS)
+    ref_g = oracle.left_product_bwd(Q, K, V, LAMS, dO)
+    for name in ("rec", "c_rec"):
+        o = FWD_IMPLS[name](Q, K, V, LAMS)
+        assert oracle.rel_max_err(o, ref_o) < 1e-12, name
+        for x, r in zip(BWD_IMPLS[name](Q, K, V, LAMS, dO), ref_g):
+            assert oracle.rel_max_err(x, r) < 1e-12, name
+
+
+# ---- 3. closed form: all-ones inputs -----------------------------------------
+@pytest.mark.parametrize("lam", LAMS)
+@pytest.mark.parametrize("impl", list(FWD_IMPLS))
+def test_all_ones_closed_form(lam, impl):
+    n, d = 23, 5
+    X = np.ones((1, 1, n, d))
+    O = FWD_IMPLS[impl](X, X, X, [lam])
+    t = np.arange(1, n + 1, dtype=np.float64)
+    # o_t[j] = sum_{s<=t} lam^(t-s) * (q_t.k_s) * v_s[j] = d * sum_{m=0}^{t-1} lam^m
+    expect = d * t if lam == 1.0 else d * (1 - lam ** t) / (1 - lam)
+    np.testing.assert_allclose(O[0, 0], np.repeat(expect[:, None], d, axis=1), rtol=1e-12)
+
+
+# ---- 4. textbook special cases -----------------------------------------------
+@pytest.mark.parametrize("impl", list(FWD_IMPLS))
+def test_lambda_one_is_tril_gemm(impl):
+    Q, K, V, dO = _rand(1, 1, 19, 6, seed=7)
+    O = FWD_IMPLS[impl](Q, K, V, [1.0])
+    expect = np.tril(Q[0, 0] @ K[0, 0].T) @ V[0, 0]
+    np.testing.assert_allclose(O[0, 0], expect, rtol=1e-11, atol=1e-12)
+    # last row is the plain (non-causal) right product q_n^T (K^T V)
+    np.testing.assert_allclose(O[0, 0, -1], Q[0, 0, -1] @ (K[0, 0].T @ V[0, 0]),
+                               rtol=1e-11, atol=1e-12)
+    dQ, dK, dV = BWD_IMPLS[impl](Q, K, V, [1.0], dO)
+    Gm = np.tril(dO[0, 0] @ V[0, 0].T)
+    Pm = np.tril(Q[0, 0] @ K[0, 0].T)
+    np.testing.assert_allclose(dQ[0, 0], Gm @ K[0, 0], rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(dK[0, 0], Gm.T @ Q[0, 0], rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(dV[0, 0], Pm.T @ dO[0, 0], rtol=1e-11, atol=1e-12)
+
+
+@pytest.mark.parametrize("impl", list(FWD_IMPLS))
+def test_single_token_and_vanishing_lambda(impl):
+    Q, K, V, dO = _rand(1, 1, 1, 4, seed=3)
+    O = FWD_IMPLS[impl](Q, K, V, [0.7])
+    np.testing.assert_allclose(O[0, 0, 0], (Q[0, 0, 0] @ K[0, 0, 0]) * V[0, 0, 0], rtol=1e-13)
+    # lam -> 0+: only the diagonal survives: o_t = (q_t.k_t) v_t
+    Q, K, V, dO = _rand(1, 1, 9, 4, seed=4)
+    O = FWD_IMPLS[impl](Q, K, V, [1e-300])
+    expect = np.sum(Q[0, 0] * K[0, 0], axis=1, keepdims=True) * V[0, 0]
+    np.testing.assert_allclose(O[0, 0], expect, rtol=1e-12, atol=1e-290)
+
+
+# ---- 5. trilinearity: <dO,O> = <dQ,Q> = <dK,K> = <dV,V> -----------------------
+@pytest.mark.parametrize("impl", list(FWD_IMPLS))
+def test_trilinearity_invariant(impl):
+    Q, K, V, dO = _rand(2, 4, 16, 4, seed=11)
+    O = FWD_IMPLS[impl](Q, K, V, LAMS)
+    dQ, dK, dV = BWD_IMPLS[impl](Q, K, V, LAMS, dO)
+    base = np.sum(dO * O)
+    for g, x in ((dQ, Q), (dK, K), (dV, V)):
+        assert abs(np.sum(g * x) - base) <= 1e-11 * abs(base)
+
+
+# ---- 6. finite differences (fp64, n <= 16) ------------------------------------
+@pytest.mark.parametrize("impl", list(BWD_IMPLS))
+def test_finite_differences(impl):
+    B, H, n, d = 1, 2, 12, 3
+    lam = [0.9, 1.0]
+    Q, K, V, dO = _rand(B, H, n, d, seed=21)
+    dQ, dK, dV = BWD_IMPLS[impl](Q, K, V, lam, dO)
+    fwd = oracle.left_product_fwd
+
+    def loss(q, k, v):
+        return float(np.sum(dO * fwd(q, k, v, lam)))
+
+    eps = 1e-6
+    rng = np.random.default_rng(5)
+    for which, grad in ((0, dQ), (1, dK), (2, dV)):
+        for _ in range(12):
+            idx = tuple(int(rng.integers(0, s)) for s in (B, H, n, d))
+            args_p = [Q.copy(), K.copy(), V.copy()]
+            args_m = [Q.copy(), K.copy(), V.copy()]
+            args_p[which][idx] += eps
+            args_m[which][idx] -= eps
+            fd = (loss(*args_p) - loss(*args_m)) / (2 * eps)
+            assert abs(fd - grad[idx]) <= 1e-7 * max(1.0, abs(grad[idx])), (which, idx)
+
+
+# ---- 7. block form == token form (Alg. 5 / Alg. 6, App. C) --------------------
+def _blocked_fwd(Q, K, V, lam, Bk):
+    """Alg. 5 restated for one scan, fp64, block length Bk (n % Bk == 0).
+    Lambda = diag(lam^1..lam^Bk) as in the algorithm box (the proof's
+    diag(1..lam^(Bk-1)) is a misprint: see test_block_form_rejects_misprint)."""
+    n, d = Q.shape
+    r = np.arange(1, Bk + 1, dtype=np.float64)
+    M = oracle.decay_matrix(Bk, lam)
+    Lam = lam ** r
+    LamInv = lam ** (Bk - r)            # lam^Bk * Lambda^-1, never via a division
+    KV = np.zeros((d, d))
+    O = np.zeros_like(Q)
+    for t in range(n // Bk):
+        sl = slice(t * Bk, (t + 1) * Bk)
+        Qt, Kt, Vt = Q[sl], K[sl], V[sl]
+        O[sl] = ((Qt @ Kt.T) * M) @ Vt + Lam[:, None] * (Qt @ KV)
+        KV = lam ** Bk * KV + (LamInv[:, None] * Kt).T @ Vt
+    return O
+
+
+def _blocked_bwd(Q, K, V, lam, dO, Bk):
+    """Alg. 6 restated for one scan, fp64."""
+    n, d = Q.shape
+    r = np.arange(1, Bk + 1, dtype=np.float64)
+    M = oracle.decay_matrix(Bk, lam)
+    Lam = lam ** r
+    LamInv = lam ** (Bk - r)
+    KV = np.zeros((d, d))
+    dKV = np.zeros((d, d))
+    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(Q), np.zeros_like(Q)
+    T = n // Bk
+    for t in range(T):
+        sl = slice(t * Bk, (t + 1) * Bk)
+        Kt, Vt, dOt = K[sl], V[sl], dO[sl]
+        dQ[sl] = ((dOt @ Vt.T) * M) @ Kt + Lam[:, None] * (dOt @ KV.T)
+        KV = lam ** Bk * KV + (LamInv[:, None] * Kt).T @ Vt
+    for t in range(T - 1, -1, -1):
+        sl = slice(t * Bk, (t + 1) * Bk)
+        Qt, Kt, Vt, dOt = Q[sl], K[sl], V[sl], dO[sl]
+        dK[sl] = ((dOt @ Vt.T) * M).T @ Qt + LamInv[:, None] * (Vt @ dKV.T)
+        dV[sl] = ((Qt @ Kt.T) * M).T @ dOt + LamInv[:, None] * (Kt @ dKV)
+        dKV = lam ** Bk * dKV + (Lam[:, None] * Qt).T @ dOt
+    return dQ, dK, dV
+
+
+@pytest.mark.parametrize("Bk", [1, 2, 4, 16])
+@pytest.mark.parametrize("lam", [1.0, 0.9, 0.3])
+def test_block_form_equals_token_form(Bk, lam):
+    n, d = 16, 4
+    Q, K, V, dO = _rand(1, 1, n, d, seed=31)
+    O_ref = oracle.c_recurrence_fwd(Q, K, V, [lam])[0, 0]
+    g_ref = [x[0, 0] for x in oracle.c_recurrence_bwd(Q, K, V, [lam], dO)]
+    O_blk = _blocked_fwd(Q[0, 0], K[0, 0], V[0, 0], lam, Bk)
+    np.testing.assert_allclose(O_blk, O_ref, rtol=1e-11, atol=1e-12)
+    for x, r in zip(_blocked_bwd(Q[0, 0], K[0, 0], V[0, 0], lam, dO[0, 0], Bk), g_ref):
+        np.testing.assert_allclose(x, r, rtol=1e-11, atol=1e-12)
+
+
+def test_block_form_rejects_misprint():
+    """With the proof's Lambda = diag(1, .., lam^(Bk-1)) the block form no
+    longer matches the token form: the algorithm box's diag(lam, .., lam^Bk)
+    is the reading to take."""
+    n, d, Bk, lam = 16, 4, 4, 0.9
+    Q, K, V, _ = _rand(1, 1, n, d, seed=33)
+    ref = oracle.recurrence_fwd(Q, K, V, [lam])[0, 0]
+    M = oracle.decay_matrix(Bk, lam)
+    r = np.arange(1, Bk + 1, dtype=np.float64)
+    wrong = lam ** (r - 1)
+    KV = np.zeros((d, d))
+    O = np.zeros((n, d))
+    for t in range(n // Bk):
+        sl = slice(t * Bk, (t + 1) * Bk)
+        O[sl] = ((Q[0, 0, sl] @ K[0, 0, sl].T) * M) @ V[0, 0, sl] + wrong[:, None] * (Q[0, 0, sl] @ KV)
+        KV = lam ** Bk * KV + ((lam ** (Bk - r))[:, None] * K[0, 0, sl]).T @ V[0, 0, sl]
+    assert np.max(np.abs(O - ref)) > 1e-2
+
+
+# ---- 8. causality --------------------------------------------------------------
+@pytest.mark.parametrize("impl", list(FWD_IMPLS))
+def test_causality(impl):
+    n, d, s = 10, 3, 6
+    Q, K, V, dO = _rand(1, 1, n, d, seed=41)
+    O0 = FWD_IMPLS[impl](Q, K, V, [0.8])
+    K2, V2 = K.copy(), V.copy()
+    K2[0, 0, s] += 1.0
+    V2[0, 0, s] -= 2.0
+    O1 = FWD_IMPLS[impl](Q, K2, V2, [0.8])
+    assert np.array_equal(O0[0, 0, :s], O1[0, 0, :s])
+    assert np.all(np.any(O0[0, 0, s:] != O1[0, 0, s:], axis=1))
+    g0 = BWD_IMPLS[impl](Q, K, V, [0.8], dO)
+    dO2 = dO.copy()
+    dO2[0, 0, s] += 1.0
+    g1 = BWD_IMPLS[impl](Q, K, V, [0.8], dO2)
+    for a, b in zip(g0[1:], g1[1:]):        # dK, dV change only at rows <= s
+        assert np.array_equal(a[0, 0, s + 1:], b[0, 0, s + 1:])
+
+
+# ---- 9. planted mistakes are caught (mistakes planted in a copy, on the CPU) ---
+def test_planted_transposed_state_fails_example_b():
+    g = load_golden("worked_example_b.txt")
+    Q, K, V = g["Q"][0, 0], g["K"][0, 0], g["V"][0, 0]
+    kv = np.zeros((2, 2))
+    O = np.zeros((2, 2))
+    for t in range(2):
+        kv = g["lambda"] * kv + np.outer(V[t], K[t])      # wrong: v k^T
+        O[t] = Q[t] @ kv
+    assert np.max(np.abs(O - g["O"][0, 0])) > 0.5
+
+
+def test_planted_exclusive_diagonal_fails_example_a():
+    g = load_golden("worked_example_a.txt")
+    Q, K, V = g["Q"][0, 0], g["K"][0, 0], g["V"][0, 0]
+    kv = np.zeros((1, 1))
+    O = np.zeros((3, 1))
+    for t in range(3):
+        O[t] = Q[t] @ kv                                    # wrong: state before update
+        kv = g["lambda"] * kv + np.outer(K[t], V[t])
+    assert np.max(np.abs(O - g["O"][0, 0])) > 0.5
