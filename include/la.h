@@ -1,0 +1,133 @@
+/*
+ * la.h - C ABI of the MI355X (gfx950) Lightning Attention library.
+ *
+ * The library computes causal linear attention with a per-head decay rate,
+ * forward and backward, with the tiled algorithm of Lightning Attention:
+ * each sequence block is split into an intra-block part computed as a masked
+ * left product and an inter-block part computed as a right product against a
+ * running d x d state (Alg. 3/4; with decay Alg. 5/6 and App. C).
+ *
+ * Result definition (per batch b and head h, lambda = lambda[h], rows t, s):
+ *
+ *     O[t]  = sum_{s <= t} lambda^(t-s) (Q[t] . K[s]) V[s]          (App. A)
+ *     dQ[t] = sum_{s <= t} lambda^(t-s) (dO[t] . V[s]) K[s]
+ *     dK[s] = sum_{t >= s} lambda^(t-s) (dO[t] . V[s]) Q[t]
+ *     dV[s] = sum_{t >= s} lambda^(t-s) (Q[t] . K[s]) dO[t]         (App. C)
+ *
+ * No 1/sqrt(d) scaling and no normalisation are applied (Sec. 3.1); lambda
+ * is a constant and receives no gradient (Sec. 4.1).
+ *
+ * Conventions common to every entry point
+ *   - Tensor arguments are DEVICE pointers owned by the caller, contiguous
+ *     [B, H, n, d] with d fastest, 16-byte aligned.  Outputs are fully
+ *     overwritten (never accumulated into).  Inputs and outputs must not alias.
+ *   - `lambda` is a HOST pointer to H floats; it is read during the call and
+ *     need not outlive it.  Every entry must be finite with 0 < lambda <= 1.
+ *   - d is 64 or 128; B, H, n >= 1; H <= LA_MAX_HEADS.  n need not be a
+ *     multiple of the tile length: the tail behaves as if zero-padded, which
+ *     is exact.
+ *   - dt = LA_BF16: tensors are bfloat16; contractions use bf16 operands with
+ *     fp32 accumulation and the running state is kept in fp32.
+ *     dt = LA_F32: tensors and all arithmetic are fp32.
+ *   - `workspace` is a DEVICE pointer to at least la_workspace_bytes(...)
+ *     bytes, 256-byte aligned, owned by the caller; it may be NULL when that
+ *     query returns 0.  Its contents are scratch (segment states) and need
+ *     not be initialised or preserved.  The library itself allocates nothing.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
+ *     Work is enqueued on it and the call returns without synchronising.
+ *   - The return value is an la_status; nothing is thrown, errno is untouched.
+ *     On any error nothing has been enqueued, except LA_ERR_LAUNCH, which
+ *     reports a failed kernel launch part-way through the call.
+ *   - Calls are thread-safe (no global mutable state apart from the optional
+ *     profiling hooks below) and results are bitwise reproducible from run to
+ *     run: no atomics are used in any reduction.
+ */
+#ifndef LA_H
+#define LA_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LA_MAX_HEADS 256
+
+typedef enum { LA_F32 = 0, LA_BF16 = 1 } la_dtype;
+
+typedef enum {
+    LA_OK = 0,
+    LA_ERR_NULL = -1,       /* a required pointer is NULL                       */
+    LA_ERR_SHAPE = -2,      /* B, H, n < 1, H > LA_MAX_HEADS, or d not 64 / 128  */
+    LA_ERR_DTYPE = -3,      /* dt is not LA_F32 or LA_BF16                      */
+    LA_ERR_LAMBDA = -4,     /* a decay rate is not finite or not in (0, 1]      */
+    LA_ERR_WORKSPACE = -5,  /* workspace NULL / misaligned / too small          */
+    LA_ERR_LAUNCH = -6,     /* a HIP launch failed                              */
+    LA_ERR_ALIGN = -7       /* a tensor pointer is not 16-byte aligned          */
+} la_status;
+
+/*
+ * Bytes of device scratch that la_fwd (is_bwd = 0) or la_bwd (is_bwd != 0)
+ * needs for this problem size.  The scratch holds the d x d fp32 states at
+ * segment boundaries when a sequence is cut into segments so that a small
+ * B*H still fills the GPU (the block recurrence of App. C, "KV_t" and
+ * "dKV_t", applied at segment instead of block granularity).  Returns 0 when
+ * no scratch is needed or when the arguments are invalid.  Pure host
+ * arithmetic: callable without a GPU.
+ */
+size_t la_workspace_bytes(int B, int H, int n, int d, la_dtype dt, int is_bwd);
+
+/*
+ * Forward pass (Alg. 5; Alg. 3 when lambda = 1):
+ *     O = lightning_attention(Q, K, V, lambda).
+ * Q, K, V: inputs; O: output; all [B, H, n, d] of type dt, device memory.
+ */
+int la_fwd(const void *Q, const void *K, const void *V,
+           const float *lambda /* host, [H] */,
+           void *O,
+           int B, int H, int n, int d, la_dtype dt,
+           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward pass (Alg. 6; Alg. 4 when lambda = 1): given dO = dLoss/dO,
+ * writes dQ, dK, dV.  Takes no saved forward context and not O (the
+ * algorithm lists O among its loads but never uses it); the forward state
+ * it needs is recomputed.
+ */
+int la_bwd(const void *Q, const void *K, const void *V,
+           const float *lambda /* host, [H] */,
+           const void *dO,
+           void *dQ, void *dK, void *dV,
+           int B, int H, int n, int d, la_dtype dt,
+           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Static, human-readable text for an la_status value. */
+const char *la_strerror(int status);
+
+/*
+ * Plan introspection (host arithmetic only): the tile length (the paper's
+ * "block size B"), the segment length in tokens and the number of segments per
+ * (batch, head) scan that la_fwd / la_bwd will use for this problem.  Any
+ * output pointer may be NULL.  Returns an la_status.
+ */
+int la_plan(int B, int H, int n, int d, la_dtype dt,
+            int *tile_len, int *segment_len, int *segments);
+
+/*
+ * Optional profiling hooks for benchmarks.  While enabled, every la_fwd /
+ * la_bwd call brackets each launch of its block-scan kernel (the kernel that
+ * runs the loops of Alg. 5 / Alg. 6) with HIP events on the call's stream.
+ * la_profile_collect waits for those events, adds up the elapsed times and
+ * launch counts recorded since the last collect, and clears them.
+ * Not thread-safe; meant for a single benchmarking thread.  At most
+ * LA_PROFILE_MAX_LAUNCHES launches are recorded between collects; further
+ * launches run normally but are not timed.
+ */
+#define LA_PROFILE_MAX_LAUNCHES 4096
+int la_profile_enable(int on);
+int la_profile_collect(double *scan_kernel_ms, int *scan_kernel_launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LA_H */

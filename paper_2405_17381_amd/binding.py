@@ -1,0 +1,159 @@
+"""Thin ctypes binding over the C ABI of libla.so (see include/la.h).
+
+Argument marshalling only: every step of the method runs in the HIP kernels.
+PyTorch is used for device memory and streams.  If the built library is
+missing this module raises; there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+LA_F32, LA_BF16 = 0, 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libla.so")
+EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_strerror", "la_plan",
+           "la_profile_enable", "la_profile_collect")
+_lib = None
+
+
+class LaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (status %d)" % (where, la_strerror(status), status))
+
+
+def load_library():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("HIP library %s is not built; run `python -c 'import __graft_entry__ as g; "
+                           "g.build()'` (or paper_2405_17381_amd/build.py) first" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    fp = ctypes.POINTER(ctypes.c_float)
+    lib.la_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+    lib.la_workspace_bytes.restype = sz
+    lib.la_fwd.argtypes = [vp, vp, vp, fp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.la_fwd.restype = ci
+    lib.la_bwd.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.la_bwd.restype = ci
+    lib.la_strerror.argtypes = [ci]
+    lib.la_strerror.restype = ctypes.c_char_p
+    ip = ctypes.POINTER(ci)
+    lib.la_plan.argtypes = [ci, ci, ci, ci, ci, ip, ip, ip]
+    lib.la_plan.restype = ci
+    lib.la_profile_enable.argtypes = [ci]
+    lib.la_profile_enable.restype = ci
+    lib.la_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ip]
+    lib.la_profile_collect.restype = ci
+    _lib = lib
+    return lib
+
+
+def la_strerror(status: int) -> str:
+    return load_library().la_strerror(int(status)).decode()
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return LA_F32
+    if t.dtype == torch.bfloat16:
+        return LA_BF16
+    raise TypeError("la: tensors must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _check(ts: Sequence[torch.Tensor]):
+    t0 = ts[0]
+    if t0.dim() != 4:
+        raise ValueError("la: tensors must be [B, H, n, d]")
+    for t in ts:
+        if not t.is_cuda:
+            raise ValueError("la: tensors must live on the GPU")
+        if t.shape != t0.shape or t.dtype != t0.dtype or t.device != t0.device:
+            raise ValueError("la: tensors must share shape, dtype and device")
+        if not t.is_contiguous():
+            raise ValueError("la: tensors must be contiguous [B, H, n, d]")
+
+
+def _lam(lam, H: int):
+    vals = [float(x) for x in lam]
+    if len(vals) != H:
+        raise ValueError("la: lambda must have H entries")
+    return (ctypes.c_float * H)(*vals)
+
+
+def la_workspace_bytes(B: int, H: int, n: int, d: int, dt: int, is_bwd: bool) -> int:
+    return int(load_library().la_workspace_bytes(B, H, n, d, dt, 1 if is_bwd else 0))
+
+
+def la_plan(B: int, H: int, n: int, d: int, dt: int) -> Tuple[int, int, int]:
+    """(tile length, segment length, segments per scan) the library will use."""
+    a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    rc = load_library().la_plan(B, H, n, d, dt, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    if rc != 0:
+        raise LaError(rc, "la_plan")
+    return a.value, b.value, c.value
+
+
+def _workspace(B, H, n, d, dt, is_bwd, device, workspace: Optional[torch.Tensor]):
+    need = la_workspace_bytes(B, H, n, d, dt, is_bwd)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    if workspace is None:
+        return None, 0, 0
+    return workspace, workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def la_fwd(Q, K, V, lam, O=None, workspace: Optional[torch.Tensor] = None):
+    """O = la_fwd(Q, K, V, lambda) on the current CUDA(HIP) stream."""
+    _check([Q, K, V])
+    B, H, n, d = Q.shape
+    if O is None:
+        O = torch.empty_like(Q)
+    else:
+        _check([Q, O])
+    dt = _dt(Q)
+    ws, ws_ptr, ws_bytes = _workspace(B, H, n, d, dt, False, Q.device, workspace)
+    with torch.cuda.device(Q.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _lam(lam, H),
+                                   O.data_ptr(), B, H, n, d, dt, ws_ptr, ws_bytes, stream)
+    if rc != 0:
+        raise LaError(rc, "la_fwd")
+    return O
+
+
+def la_bwd(Q, K, V, lam, dO, dQ=None, dK=None, dV=None, workspace: Optional[torch.Tensor] = None):
+    """(dQ, dK, dV) = la_bwd(Q, K, V, lambda, dO) on the current stream."""
+    _check([Q, K, V, dO])
+    B, H, n, d = Q.shape
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    _check([Q, dQ, dK, dV])
+    dt = _dt(Q)
+    ws, ws_ptr, ws_bytes = _workspace(B, H, n, d, dt, True, Q.device, workspace)
+    with torch.cuda.device(Q.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _lam(lam, H),
+                                   dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                                   B, H, n, d, dt, ws_ptr, ws_bytes, stream)
+    if rc != 0:
+        raise LaError(rc, "la_bwd")
+    return dQ, dK, dV
+
+
+def la_profile_enable(on: bool) -> None:
+    load_library().la_profile_enable(1 if on else 0)
+
+
+def la_profile_collect() -> Tuple[float, int]:
+    """(total ms, launches) of the block-scan kernel since the last collect."""
+    ms, cnt = ctypes.c_double(), ctypes.c_int()
+    load_library().la_profile_collect(ctypes.byref(ms), ctypes.byref(cnt))
+    return ms.value, cnt.value

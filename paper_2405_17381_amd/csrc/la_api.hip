@@ -1,0 +1,307 @@
+// C ABI of the library: argument checks, launch planning and kernel launches.
+// Declarations and the contract of every entry point are in include/la.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdlib>
+#include <mutex>
+
+#include "la_common.h"
+#include "la_kernels_bf16.h"
+#include "la_kernels_f32.h"
+
+namespace {
+
+// MI355X: 256 compute units.  The planner is pure host arithmetic on purpose
+// (the workspace query must give the same answer with or without a GPU).
+constexpr int kComputeUnits = 256;
+constexpr int kTargetWorkgroups = 2 * kComputeUnits;
+constexpr int kMinSegmentTokens = 512;
+
+struct Plan {
+    int tile;       // block length BK (the paper's "block size B")
+    int L;          // segment length in tokens (multiple of tile)
+    int S;          // segments per scan
+};
+
+int tile_len(int d, la_dtype dt)
+{
+    if (dt == LA_BF16) return 64;
+    return d == 64 ? 64 : 32;
+}
+
+int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+Plan make_plan(int B, int H, int n, int d, la_dtype dt)
+{
+    Plan p;
+    p.tile = tile_len(d, dt);
+    const long scans = (long)B * H;
+    int L = round_up(n, p.tile);
+    if (scans < kTargetWorkgroups) {
+        const long want = (kTargetWorkgroups + scans - 1) / scans;   // segments wanted per scan
+        long l = (n + want - 1) / want;
+        if (l < kMinSegmentTokens) l = kMinSegmentTokens;
+        l = round_up((int)l, p.tile);
+        if (l < L) L = (int)l;
+    }
+    // tuning / test override: segment length in tokens
+    if (const char *e = std::getenv("LA_LSEG")) {
+        long v = std::atol(e);
+        if (v > 0) {
+            v = round_up((int)(v > (1 << 30) ? (1 << 30) : v), p.tile);
+            L = (int)(v < round_up(n, p.tile) ? v : round_up(n, p.tile));
+        }
+    }
+    p.L = L;
+    p.S = (n + L - 1) / L;
+    return p;
+}
+
+int check_common(int B, int H, int n, int d, la_dtype dt)
+{
+    if (dt != LA_F32 && dt != LA_BF16) return LA_ERR_DTYPE;
+    if (B < 1 || H < 1 || n < 1 || H > LA_MAX_HEADS) return LA_ERR_SHAPE;
+    if (d != 64 && d != 128) return LA_ERR_SHAPE;
+    if ((long)B * H > (long)INT32_MAX / 4096) return LA_ERR_SHAPE;
+    return LA_OK;
+}
+
+int check_lambda(const float *lambda, int H, LaLambdas *out)
+{
+    for (int h = 0; h < H; ++h) {
+        const float l = lambda[h];
+        if (!std::isfinite(l) || !(l > 0.0f) || !(l <= 1.0f)) return LA_ERR_LAMBDA;
+        out->v[h] = l;
+        out->lg2[h] = (float)std::log2((double)l);
+    }
+    for (int h = H; h < LA_MAX_HEADS; ++h) { out->v[h] = 1.0f; out->lg2[h] = 0.0f; }
+    return LA_OK;
+}
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+size_t state_bytes(const Plan &p, int B, int H, int d)
+{
+    if (p.S <= 1) return 0;
+    return (size_t)B * H * p.S * (size_t)d * d * sizeof(float);
+}
+
+// ---- profiling hooks (single benchmarking thread) ---------------------------
+struct Profile {
+    bool on = false;
+    int count = 0;
+    hipEvent_t start[LA_PROFILE_MAX_LAUNCHES];
+    hipEvent_t stop[LA_PROFILE_MAX_LAUNCHES];
+    int created = 0;
+} g_prof;
+
+struct ScopedTimer {
+    hipStream_t s;
+    int slot = -1;
+    explicit ScopedTimer(hipStream_t st) : s(st)
+    {
+        if (!g_prof.on || g_prof.count >= LA_PROFILE_MAX_LAUNCHES) return;
+        slot = g_prof.count++;
+        if (slot >= g_prof.created) {
+            if (hipEventCreate(&g_prof.start[slot]) != hipSuccess ||
+                hipEventCreate(&g_prof.stop[slot]) != hipSuccess) { slot = -1; g_prof.count--; return; }
+            g_prof.created = slot + 1;
+        }
+        (void)hipEventRecord(g_prof.start[slot], s);
+    }
+    ~ScopedTimer() { if (slot >= 0) (void)hipEventRecord(g_prof.stop[slot], s); }
+};
+
+// ---- kernel launch helpers ----------------------------------------------------
+template <typename K>
+hipError_t allow_lds(K kernel, size_t bytes)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+template <int D, bool REV, bool STATE_ONLY>
+hipError_t launch_bf16(const ScanArgs &a, const LaLambdas &lams, long scans, hipStream_t s)
+{
+    using Cfg = Bf16Cfg<D>;
+    auto kern = la_scan_bf16<D, REV, STATE_ONLY>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
+    if (attr_err != hipSuccess) return attr_err;
+    dim3 grid((unsigned)(scans * a.S)), block(Cfg::NT);
+    hipLaunchKernelGGL(kern, grid, block, Cfg::lds_bytes, s, a, lams);
+    return hipGetLastError();
+}
+
+template <int D, int BK, bool REV, bool STATE_ONLY>
+hipError_t launch_f32(const ScanArgs &a, const LaLambdas &lams, long scans, hipStream_t s)
+{
+    using Cfg = F32Cfg<D, BK>;
+    auto kern = la_scan_f32<D, BK, REV, STATE_ONLY>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
+    if (attr_err != hipSuccess) return attr_err;
+    dim3 grid((unsigned)(scans * a.S)), block(Cfg::NT);
+    hipLaunchKernelGGL(kern, grid, block, Cfg::lds_bytes, s, a, lams);
+    return hipGetLastError();
+}
+
+template <bool REV, bool STATE_ONLY>
+hipError_t launch_scan_kernel(const ScanArgs &a, const LaLambdas &lams, long scans, int d,
+                              la_dtype dt, hipStream_t s)
+{
+    if (dt == LA_BF16) {
+        if (d == 64) return launch_bf16<64, REV, STATE_ONLY>(a, lams, scans, s);
+        return launch_bf16<128, REV, STATE_ONLY>(a, lams, scans, s);
+    }
+    if (d == 64) return launch_f32<64, 64, REV, STATE_ONLY>(a, lams, scans, s);
+    return launch_f32<128, 32, REV, STATE_ONLY>(a, lams, scans, s);
+}
+
+// One decayed causal scan Out = scan(A, Bm, C): [segment states -> segment scan ->] block scan.
+template <bool REV>
+int run_scan(const void *A, const void *Bm, const void *C, void *Out, const LaLambdas &lams,
+             const Plan &p, int B, int H, int n, int d, la_dtype dt, float *states, hipStream_t s)
+{
+    const long scans = (long)B * H;
+    ScanArgs a;
+    a.A = A; a.Bm = Bm; a.C = C; a.Out = Out;
+    a.states = p.S > 1 ? states : nullptr;
+    a.n = n; a.H = H; a.L = p.L; a.S = p.S;
+    if (p.S > 1) {
+        if (launch_scan_kernel<REV, true>(a, lams, scans, d, dt, s) != hipSuccess) return LA_ERR_LAUNCH;
+        SegScanArgs sa;
+        sa.states = states; sa.H = H; sa.S = p.S; sa.L = p.L; sa.DD = d * d;
+        dim3 grid((unsigned)((d * d + 255) / 256), (unsigned)scans), block(256);
+        hipLaunchKernelGGL(la_segment_scan<REV>, grid, block, 0, s, sa, lams);
+        if (hipGetLastError() != hipSuccess) return LA_ERR_LAUNCH;
+    }
+    {
+        ScopedTimer t(s);
+        if (launch_scan_kernel<REV, false>(a, lams, scans, d, dt, s) != hipSuccess) return LA_ERR_LAUNCH;
+    }
+    return LA_OK;
+}
+
+int check_workspace(const Plan &p, int B, int H, int d, void *workspace, size_t workspace_bytes)
+{
+    const size_t need = state_bytes(p, B, H, d);
+    if (need == 0) return LA_OK;
+    if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < need)
+        return LA_ERR_WORKSPACE;
+    return LA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t la_workspace_bytes(int B, int H, int n, int d, la_dtype dt, int is_bwd)
+{
+    (void)is_bwd;   // the three backward scans run one after another and share the scratch
+    if (check_common(B, H, n, d, dt) != LA_OK) return 0;
+    return state_bytes(make_plan(B, H, n, d, dt), B, H, d);
+}
+
+int la_plan(int B, int H, int n, int d, la_dtype dt, int *tile, int *segment_len, int *segments)
+{
+    int rc = check_common(B, H, n, d, dt);
+    if (rc != LA_OK) return rc;
+    const Plan p = make_plan(B, H, n, d, dt);
+    if (tile) *tile = p.tile;
+    if (segment_len) *segment_len = p.L;
+    if (segments) *segments = p.S;
+    return LA_OK;
+}
+
+int la_fwd(const void *Q, const void *K, const void *V, const float *lambda, void *O,
+           int B, int H, int n, int d, la_dtype dt,
+           void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_common(B, H, n, d, dt);
+    if (rc != LA_OK) return rc;
+    if (!Q || !K || !V || !O || !lambda) return LA_ERR_NULL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return LA_ERR_ALIGN;
+    LaLambdas lams;
+    rc = check_lambda(lambda, H, &lams);
+    if (rc != LA_OK) return rc;
+    const Plan p = make_plan(B, H, n, d, dt);
+    rc = check_workspace(p, B, H, d, workspace, workspace_bytes);
+    if (rc != LA_OK) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    // O = scan(Q, K, V)                                                   (Alg. 5)
+    return run_scan<false>(Q, K, V, O, lams, p, B, H, n, d, dt, (float *)workspace, s);
+}
+
+int la_bwd(const void *Q, const void *K, const void *V, const float *lambda, const void *dO,
+           void *dQ, void *dK, void *dV,
+           int B, int H, int n, int d, la_dtype dt,
+           void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_common(B, H, n, d, dt);
+    if (rc != LA_OK) return rc;
+    if (!Q || !K || !V || !dO || !dQ || !dK || !dV || !lambda) return LA_ERR_NULL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(dO) ||
+        !aligned16(dQ) || !aligned16(dK) || !aligned16(dV)) return LA_ERR_ALIGN;
+    LaLambdas lams;
+    rc = check_lambda(lambda, H, &lams);
+    if (rc != LA_OK) return rc;
+    const Plan p = make_plan(B, H, n, d, dt);
+    rc = check_workspace(p, B, H, d, workspace, workspace_bytes);
+    if (rc != LA_OK) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    float *ws = (float *)workspace;
+    // dQ = scan(dO, V, K): first loop of Alg. 6, state = KV^T
+    rc = run_scan<false>(dO, V, K, dQ, lams, p, B, H, n, d, dt, ws, s);
+    if (rc != LA_OK) return rc;
+    // dK = scan_rev(V, dO, Q): second loop of Alg. 6, state = dKV^T
+    rc = run_scan<true>(V, dO, Q, dK, lams, p, B, H, n, d, dt, ws, s);
+    if (rc != LA_OK) return rc;
+    // dV = scan_rev(K, Q, dO): second loop of Alg. 6, state = dKV
+    return run_scan<true>(K, Q, dO, dV, lams, p, B, H, n, d, dt, ws, s);
+}
+
+const char *la_strerror(int status)
+{
+    switch (status) {
+    case LA_OK: return "ok";
+    case LA_ERR_NULL: return "a required pointer is NULL";
+    case LA_ERR_SHAPE: return "invalid shape: need B,H,n >= 1, H <= 256, d in {64,128}";
+    case LA_ERR_DTYPE: return "invalid dtype";
+    case LA_ERR_LAMBDA: return "decay rate not finite or outside (0, 1]";
+    case LA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case LA_ERR_LAUNCH: return "HIP kernel launch failed";
+    case LA_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
+    default: return "unknown status";
+    }
+}
+
+int la_profile_enable(int on)
+{
+    g_prof.on = on != 0;
+    return LA_OK;
+}
+
+int la_profile_collect(double *scan_kernel_ms, int *scan_kernel_launches)
+{
+    double total = 0.0;
+    int ok = 0;
+    for (int i = 0; i < g_prof.count; ++i) {
+        if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess) continue;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]) == hipSuccess) {
+            total += ms;
+            ++ok;
+        }
+    }
+    g_prof.count = 0;
+    if (scan_kernel_ms) *scan_kernel_ms = total;
+    if (scan_kernel_launches) *scan_kernel_launches = ok;
+    return LA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,60 @@
+// Shared declarations of the HIP kernels (gfx950 only).
+//
+// Every kernel here evaluates one "decayed causal scan"
+//
+//     Out[t] = sum_{s <= t} lambda^(t-s) (A[t] . Bm[s]) C[s]        (forward in time)
+//     Out[t] = sum_{s >= t} lambda^(s-t) (A[t] . Bm[s]) C[s]        (REV, backward in time)
+//
+// over one (batch, head) slice of [n, D] tensors, tiled as in Alg. 5 / Alg. 6:
+// per block an intra part [(A Bm^T) * M] C and an inter part against a running
+// D x D state  St[i][j] = sum_s w_s Bm[s][i] C[s][j].  The four results of the
+// method are this scan with different operands:
+//
+//     O  = scan(Q,  K,  V )            dQ = scan(dO, V,  K )         (Alg. 6, first loop)
+//     dK = scan_rev(V, dO, Q)          dV = scan_rev(K, Q, dO)       (Alg. 6, second loop)
+//
+// State normalisation.  With 0-based row r inside a block of BK rows starting
+// at t0, the forward state at a block start weights the immediately preceding
+// token by 1:  St = sum_{s < t0} lambda^(t0-1-s) Bm[s] C[s]^T  (the paper's KV_t).
+// The reverse state weights the immediately following token by 1:
+// St = sum_{s >= t0+BK} lambda^(s-t0-BK) Bm[s] C[s]^T; the paper's dKV_t carries
+// one more factor lambda, which it takes back in its row scale lambda^(B-r);
+// the products are identical.
+//
+//   forward : mask lambda^(r-c) (r >= c), inter row scale lambda^(r+1),
+//             state update weight of row r: lambda^(BK-1-r)
+//   reverse : mask lambda^(c-r) (c >= r), inter row scale lambda^(BK-r),
+//             state update weight of row r: lambda^r
+//   both    : St <- lambda^BK St + sum_r weight_r Bm[r] C[r]^T
+// No negative power of lambda is ever formed (Lambda^-1 of Alg. 5 would
+// overflow for small lambda).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/la.h"
+
+struct LaLambdas {
+    float v[LA_MAX_HEADS];      // lambda_h
+    float lg2[LA_MAX_HEADS];    // log2(lambda_h), evaluated in double on the host
+};
+
+struct ScanArgs {
+    const void *A;       // role of Q   [scans, n, D]
+    const void *Bm;      // role of K
+    const void *C;       // role of V
+    void *Out;           // role of O
+    float *states;       // [scans, S, D*D] fp32 segment-boundary states (or nullptr)
+    int n;               // sequence length
+    int H;               // heads (scan index % H selects lambda)
+    int L;               // segment length in tokens (multiple of the tile length)
+    int S;               // segments per scan
+};
+
+// Segment scan over local segment states, in place:
+//   forward: W[s] <- state entering segment s  (W[0] <- 0)
+//   reverse: W[s] <- state entering segment s from the right (W[S-1] <- 0)
+struct SegScanArgs {
+    float *states;       // [scans, S, DD]
+    int H, S, L, DD;
+};

@@ -1,0 +1,341 @@
+// bf16 path: the block loop of Alg. 5 / Alg. 6 on gfx950 matrix cores.
+//
+// One workgroup of D/32 wavefronts walks the blocks (BK = 64 rows) of one
+// segment of one (batch, head) scan.  All four contractions of a block run on
+// v_mfma_f32_32x32x16_bf16 with fp32 accumulation:
+//
+//   S^T = Bm A^T           (scores, transposed; contraction over the feature dim)
+//   Out = P C              (intra block, P = bf16(S * decay mask))
+//   Out+= rowscale * A St  (inter block, against the running state)
+//   St  = lambda^BK St + (w * Bm)^T C
+//
+// Ownership.  Wave w owns the value-feature slice j in [32w, 32w+32): its
+// columns of Out and of the state St[:, slice].  The state never leaves the
+// wave's accumulator registers: the fp32 accumulator layout of a 32x32 tile
+// (lane = column, registers = rows) is exactly an MFMA B operand with a
+// permuted contraction order, so it is rounded to bf16 in registers and fed
+// straight back; the A operand (rows of the A tile in LDS) is read with the
+// same permutation.
+//
+// LDS tiles per block: A and Bm row-major (for the feature-dim contraction),
+// C^T and (w*Bm)^T transposed (for the token-dim contractions; the transpose
+// is done in registers while staging), P row-major, and the Out tile reuses
+// A's storage so that global stores are full 16-byte rows.
+//
+// MFMA 32x32x16 bf16 register layout used throughout (lane l, i = l % 32,
+// g = l / 32):  A operand: row i, k = 8g + e (e = 0..7);  B operand: column i,
+// k = 8g + e;  C/D: column i, register v holds row 8*(v/4) + 4g + v%4.
+#pragma once
+#include "la_common.h"
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+typedef uint32_t U4 __attribute__((ext_vector_type(4)));   // 16 bytes = 8 bf16
+typedef uint32_t U2 __attribute__((ext_vector_type(2)));   //  8 bytes = 4 bf16
+
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi)
+{
+    f32x2_t v = {lo, hi};
+    bf16x2_t r = __builtin_convertvector(v, bf16x2_t);   // round-to-nearest-even
+    return __builtin_bit_cast(uint32_t, r);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ f32x16_t mfma32(const U4 &a, const U4 &b, f32x16_t c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                   __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
+template <int D>
+struct Bf16Cfg {
+    static constexpr int BK = 64;
+    static constexpr int NW = D / 32;          // wavefronts per workgroup
+    static constexpr int NT = NW * 64;
+    static constexpr int LDN = D + 8;          // row stride of row-major tiles (elements)
+    static constexpr int LDT = BK + 8;         // row stride of transposed tiles
+    static constexpr int LDP = BK + 8;
+    static constexpr int nA = BK * LDN, nB = BK * LDN, nBT = D * LDT, nCT = D * LDT, nP = BK * LDP;
+    static constexpr size_t lds_bytes = 2 * (size_t)(nA + nB + nBT + nCT + nP);
+};
+
+template <int D, bool REV, bool STATE_ONLY>
+__global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas lams)
+{
+    using Cfg = Bf16Cfg<D>;
+    constexpr int BK = Cfg::BK, NW = Cfg::NW, NT = Cfg::NT;
+    constexpr int LDN = Cfg::LDN, LDT = Cfg::LDT, LDP = Cfg::LDP;
+    constexpr int KS_D = D / 16;               // k-steps over the feature dim
+    constexpr int KS_B = BK / 16;              // k-steps over the block rows (= 4)
+    constexpr int MT_D = D / 32;               // 32-row tiles over the feature dim
+    constexpr int CH = D / 8;                  // 16-byte chunks per row
+    constexpr int NTILE = (3 + NW - 1) / NW;   // score tiles per wave (3 non-zero tiles)
+
+    extern __shared__ __align__(16) uint16_t smem_bf16[];
+    uint16_t *sA = smem_bf16;
+    uint16_t *sB = sA + Cfg::nA;
+    uint16_t *sBT = sB + Cfg::nB;
+    uint16_t *sCT = sBT + Cfg::nBT;
+    uint16_t *sP = sCT + Cfg::nCT;
+
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, l = tid & 63, l32 = l & 31, g = l >> 5;
+    const int sa = tid / CH, sc = tid % CH;    // staging: rows 4sa..4sa+3, chunk sc
+
+    const int seg = blockIdx.x % a.S;
+    const int scan = blockIdx.x / a.S;
+    if (STATE_ONLY) {
+        if (!REV && seg == a.S - 1) return;    // never consumed
+        if (REV && seg == 0) return;
+    }
+    const float lg = lams.lg2[scan % a.H];
+    auto pw = [lg](int k) -> float { return exp2f((float)k * lg); };
+
+    const int seg_lo = seg * a.L;
+    const int seg_hi = min(a.n, seg_lo + a.L);
+    const int nblk = (seg_hi - seg_lo + BK - 1) / BK;
+
+    const size_t base = (size_t)scan * a.n * D;
+    const uint16_t *gA = (const uint16_t *)a.A + base;
+    const uint16_t *gB = (const uint16_t *)a.Bm + base;
+    const uint16_t *gC = (const uint16_t *)a.C + base;
+    uint16_t *gO = (uint16_t *)a.Out + base;
+    float *gSt = a.states ? a.states + ((size_t)scan * a.S + seg) * (size_t)(D * D) : nullptr;
+
+    // ---- per-lane constants --------------------------------------------------
+    float wst[4];                              // state-update weight of staged rows
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int r = 4 * sa + i;
+        wst[i] = REV ? pw(r) : pw(BK - 1 - r);
+    }
+    const float lamBK = pw(BK);
+    float rs16[16];                            // inter-block row scale inside a 32-row tile
+    float rs_tile[2];
+    float mk[NTILE][16];                       // decay mask of this wave's score tiles
+    if (!STATE_ONLY) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            int ql = 8 * (v >> 2) + 4 * g + (v & 3);
+            rs16[v] = REV ? pw(32 - ql) : pw(ql + 1);
+        }
+        rs_tile[0] = REV ? pw(32) : 1.0f;
+        rs_tile[1] = REV ? 1.0f : pw(32);
+#pragma unroll
+        for (int ti = 0; ti < NTILE; ++ti) {
+            int tile = w + ti * NW;            // 0,1,2 -> (kt,qt)
+            int kt = REV ? (tile >= 1) : (tile == 2);
+            int qt = REV ? (tile == 2) : (tile >= 1);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int key = 32 * kt + 8 * (v >> 2) + 4 * g + (v & 3);
+                int q = 32 * qt + l32;
+                int dist = REV ? (key - q) : (q - key);
+                mk[ti][v] = (dist >= 0) ? pw(dist) : 0.0f;
+            }
+        }
+    }
+
+    // ---- running state: St[i][j], j in this wave's slice ----------------------
+    f32x16_t st[MT_D];
+    const bool has_init = !STATE_ONLY && a.S > 1 && gSt != nullptr;
+#pragma unroll
+    for (int mt = 0; mt < MT_D; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            int i = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
+            st[mt][v] = has_init ? gSt[(size_t)i * D + 32 * w + l32] : 0.0f;
+        }
+    U4 sf[KS_D];                               // bf16 copy of the state as MFMA B operand
+    auto refresh_state_operand = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < KS_D; ++ks) {
+            const int mt = ks >> 1, h8 = 8 * (ks & 1);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                sf[ks][e] = pack2_bf16(st[mt][h8 + 2 * e], st[mt][h8 + 2 * e + 1]);
+        }
+    };
+    if (!STATE_ONLY) refresh_state_operand();
+
+    // ---- global -> register prefetch of one block -------------------------------
+    U4 ra[4], rb[4], rc[4];
+    auto load_block = [&](int blk) {
+        const int t0 = seg_lo + blk * BK;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int t = t0 + 4 * sa + i;
+            const size_t off = (size_t)min(t, seg_hi - 1) * D + 8 * sc;
+            // rows past the segment end read a valid row and are zeroed (zero padding)
+            const bool ok = t < seg_hi;
+            const U4 z = {0u, 0u, 0u, 0u};
+            rb[i] = *(const U4 *)(gB + off);
+            rc[i] = *(const U4 *)(gC + off);
+            rb[i] = ok ? rb[i] : z;
+            rc[i] = ok ? rc[i] : z;
+            if (!STATE_ONLY) {
+                ra[i] = *(const U4 *)(gA + off);
+                ra[i] = ok ? ra[i] : z;
+            }
+        }
+    };
+    // ---- registers -> LDS, transposing C and the weighted Bm ---------------------
+    auto stage_block = [&]() {
+        if (!STATE_ONLY) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                *(U4 *)(sA + (4 * sa + i) * LDN + 8 * sc) = ra[i];
+                *(U4 *)(sB + (4 * sa + i) * LDN + 8 * sc) = rb[i];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            // element e of each of the 4 rows -> 4 consecutive block rows of feature 8sc+e
+            float b0, b1, b2, b3;
+            uint32_t c0, c1, c2, c3;
+            if (e & 1) {
+                b0 = bf16_hi(rb[0][e >> 1]); b1 = bf16_hi(rb[1][e >> 1]);
+                b2 = bf16_hi(rb[2][e >> 1]); b3 = bf16_hi(rb[3][e >> 1]);
+                c0 = rc[0][e >> 1] >> 16; c1 = rc[1][e >> 1] >> 16;
+                c2 = rc[2][e >> 1] >> 16; c3 = rc[3][e >> 1] >> 16;
+            } else {
+                b0 = bf16_lo(rb[0][e >> 1]); b1 = bf16_lo(rb[1][e >> 1]);
+                b2 = bf16_lo(rb[2][e >> 1]); b3 = bf16_lo(rb[3][e >> 1]);
+                c0 = rc[0][e >> 1] & 0xffffu; c1 = rc[1][e >> 1] & 0xffffu;
+                c2 = rc[2][e >> 1] & 0xffffu; c3 = rc[3][e >> 1] & 0xffffu;
+            }
+            U2 tb, tc;
+            tb[0] = pack2_bf16(b0 * wst[0], b1 * wst[1]);
+            tb[1] = pack2_bf16(b2 * wst[2], b3 * wst[3]);
+            tc[0] = c0 | (c1 << 16);
+            tc[1] = c2 | (c3 << 16);
+            *(U2 *)(sBT + (8 * sc + e) * LDT + 4 * sa) = tb;
+            *(U2 *)(sCT + (8 * sc + e) * LDT + 4 * sa) = tc;
+        }
+    };
+
+    load_block(REV ? nblk - 1 : 0);
+
+    for (int ib = 0; ib < nblk; ++ib) {
+        const int blk = REV ? (nblk - 1 - ib) : ib;
+        const int t0 = seg_lo + blk * BK;
+        __syncthreads();                        // previous block's LDS readers are done
+        stage_block();
+        __syncthreads();
+        if (ib + 1 < nblk) load_block(REV ? blk - 1 : blk + 1);
+
+        // C^T fragments of this wave's slice: B operand of P C and of the state update
+        U4 cf[KS_B];
+#pragma unroll
+        for (int ks = 0; ks < KS_B; ++ks)
+            cf[ks] = *(const U4 *)(sCT + (32 * w + l32) * LDT + 16 * ks + 8 * g);
+
+        f32x16_t acc[2];
+        if (!STATE_ONLY) {
+            // ---- scores: S^T tile (kt, qt) = Bm[kt] A[qt]^T, masked, to LDS as P[q][key]
+#pragma unroll
+            for (int ti = 0; ti < NTILE; ++ti) {
+                const int tile = w + ti * NW;
+                if (tile < 3) {
+                    const int kt = REV ? (tile >= 1) : (tile == 2);
+                    const int qt = REV ? (tile == 2) : (tile >= 1);
+                    f32x16_t s = {0};
+#pragma unroll
+                    for (int ks = 0; ks < KS_D; ++ks) {
+                        U4 fa = *(const U4 *)(sB + (32 * kt + l32) * LDN + 16 * ks + 8 * g);
+                        U4 fb = *(const U4 *)(sA + (32 * qt + l32) * LDN + 16 * ks + 8 * g);
+                        s = mfma32(fa, fb, s);
+                    }
+#pragma unroll
+                    for (int v4 = 0; v4 < 4; ++v4) {
+                        U2 p;
+                        p[0] = pack2_bf16(s[4 * v4 + 0] * mk[ti][4 * v4 + 0],
+                                            s[4 * v4 + 1] * mk[ti][4 * v4 + 1]);
+                        p[1] = pack2_bf16(s[4 * v4 + 2] * mk[ti][4 * v4 + 2],
+                                            s[4 * v4 + 3] * mk[ti][4 * v4 + 3]);
+                        *(U2 *)(sP + (32 * qt + l32) * LDP + 32 * kt + 8 * v4 + 4 * g) = p;
+                    }
+                }
+            }
+            // ---- inter block: acc = rowscale * (A St), state operand from registers
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                f32x16_t x = {0};
+#pragma unroll
+                for (int ks = 0; ks < KS_D; ++ks) {
+                    const uint16_t *row = sA + (32 * mt + l32) * LDN + 16 * ks + 4 * g;
+                    U2 lo = *(const U2 *)(row);
+                    U2 hi = *(const U2 *)(row + 8);
+                    U4 fa = {lo[0], lo[1], hi[0], hi[1]};
+                    x = mfma32(fa, sf[ks], x);
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) x[v] *= rs16[v] * rs_tile[mt];
+                acc[mt] = x;
+            }
+            __syncthreads();                    // P is complete
+            // ---- intra block: acc += P C
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+                for (int ks = 0; ks < KS_B; ++ks) {
+                    const int ktile = ks >> 1;
+                    const bool live = REV ? (ktile >= mt) : (ktile <= mt);
+                    if (live) {
+                        U4 fa = *(const U4 *)(sP + (32 * mt + l32) * LDP + 16 * ks + 8 * g);
+                        acc[mt] = mfma32(fa, cf[ks], acc[mt]);
+                    }
+                }
+            }
+        }
+
+        // ---- state update: St = lambda^BK St + (w Bm)^T C ---------------------------
+#pragma unroll
+        for (int mt = 0; mt < MT_D; ++mt) {
+            f32x16_t s = st[mt];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[v] *= lamBK;
+#pragma unroll
+            for (int ks = 0; ks < KS_B; ++ks) {
+                U4 fa = *(const U4 *)(sBT + (32 * mt + l32) * LDT + 16 * ks + 8 * g);
+                s = mfma32(fa, cf[ks], s);
+            }
+            st[mt] = s;
+        }
+
+        if (!STATE_ONLY) {
+            refresh_state_operand();
+            __syncthreads();                    // all waves are done reading A and P
+            // ---- Out tile -> LDS (A's storage) as bf16, then full-row global stores
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int q = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
+                    const uint32_t pk = pack2_bf16(acc[mt][v], 0.0f);
+                    sA[q * LDN + 32 * w + l32] = (uint16_t)(pk & 0xffffu);
+                }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int t = t0 + 4 * sa + i;
+                if (t < seg_hi)
+                    *(U4 *)(gO + (size_t)t * D + 8 * sc) = *(const U4 *)(sA + (4 * sa + i) * LDN + 8 * sc);
+            }
+        }
+    }
+
+    if (STATE_ONLY) {
+#pragma unroll
+        for (int mt = 0; mt < MT_D; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int i = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
+                gSt[(size_t)i * D + 32 * w + l32] = st[mt][v];
+            }
+    }
+}

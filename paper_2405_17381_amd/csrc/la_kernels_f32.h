@@ -1,0 +1,215 @@
+// fp32 path: the block loop of Alg. 5 / Alg. 6 taken literally, all-fp32 FMA
+// arithmetic, one workgroup of 256 threads per (scan, segment).  Tiles of A,
+// Bm, C, the masked score tile and the running state all live in LDS.
+// This path exists for fp32 parity (tolerance 1e-4), not for speed.
+#pragma once
+#include "la_common.h"
+
+template <int D, int BK>
+struct F32Cfg {
+    static constexpr int NT = 256;
+    static constexpr int LD = D + 1;            // padded row stride (floats)
+    static constexpr int LS = BK + 1;
+    static constexpr int RI = BK / 16;          // block rows per thread
+    static constexpr int CJ = D / 16;           // feature columns per thread
+    static constexpr size_t lds_bytes =
+        sizeof(float) * (size_t)(3 * BK * LD + BK * LS + D * LD + (BK + 1));
+};
+
+template <int D, int BK, bool REV, bool STATE_ONLY>
+__global__ __launch_bounds__(256) void la_scan_f32(ScanArgs a, LaLambdas lams)
+{
+    using Cfg = F32Cfg<D, BK>;
+    constexpr int LD = Cfg::LD, LS = Cfg::LS, RI = Cfg::RI, CJ = Cfg::CJ;
+    extern __shared__ float smem_f32[];
+    float *sA = smem_f32;
+    float *sB = sA + BK * LD;
+    float *sC = sB + BK * LD;
+    float *sS = sC + BK * LD;
+    float *sKV = sS + BK * LS;
+    float *sPw = sKV + D * LD;
+
+    const int tid = threadIdx.x;
+    const int ty = tid >> 4, tx = tid & 15;
+    const int seg = blockIdx.x % a.S;
+    const int scan = blockIdx.x / a.S;
+    const float lam = lams.v[scan % a.H];
+
+    const int seg_lo = seg * a.L;
+    const int seg_hi = min(a.n, seg_lo + a.L);
+    if (STATE_ONLY) {
+        // the state leaving the last (forward) / first (reverse) segment is never used
+        if (!REV && seg == a.S - 1) return;
+        if (REV && seg == 0) return;
+    }
+    const int nblk = (seg_hi - seg_lo + BK - 1) / BK;
+
+    const float *gA = (const float *)a.A + (size_t)scan * a.n * D;
+    const float *gB = (const float *)a.Bm + (size_t)scan * a.n * D;
+    const float *gC = (const float *)a.C + (size_t)scan * a.n * D;
+    float *gO = (float *)a.Out + (size_t)scan * a.n * D;
+    float *gSt = a.states ? a.states + ((size_t)scan * a.S + seg) * (size_t)(D * D) : nullptr;
+
+    // lambda^k, k = 0..BK, evaluated in double then rounded once
+    for (int k = tid; k <= BK; k += 256) sPw[k] = (float)pow((double)lam, (double)k);
+    // initial state
+    const bool has_init = !STATE_ONLY && a.S > 1 && gSt != nullptr;
+    for (int e = tid; e < D * D; e += 256) {
+        int i = e / D, j = e % D;
+        sKV[i * LD + j] = has_init ? gSt[e] : 0.0f;
+    }
+    __syncthreads();
+    const float lamBK = sPw[BK];
+
+    for (int ib = 0; ib < nblk; ++ib) {
+        const int blk = REV ? (nblk - 1 - ib) : ib;
+        const int t0 = seg_lo + blk * BK;
+        // ---- load tiles (rows past the segment end are zero) ----
+        for (int e = tid; e < BK * (D / 4); e += 256) {
+            int r = e / (D / 4), c4 = (e % (D / 4)) * 4;
+            int t = t0 + r;
+            float4 vb = make_float4(0.f, 0.f, 0.f, 0.f), vc = vb, va = vb;
+            if (t < seg_hi) {
+                vb = *(const float4 *)(gB + (size_t)t * D + c4);
+                vc = *(const float4 *)(gC + (size_t)t * D + c4);
+                if (!STATE_ONLY) va = *(const float4 *)(gA + (size_t)t * D + c4);
+            }
+            float *pb = sB + r * LD + c4, *pc = sC + r * LD + c4, *pa = sA + r * LD + c4;
+            pb[0] = vb.x; pb[1] = vb.y; pb[2] = vb.z; pb[3] = vb.w;
+            pc[0] = vc.x; pc[1] = vc.y; pc[2] = vc.z; pc[3] = vc.w;
+            if (!STATE_ONLY) { pa[0] = va.x; pa[1] = va.y; pa[2] = va.z; pa[3] = va.w; }
+        }
+        __syncthreads();
+
+        if (!STATE_ONLY) {
+            // ---- masked scores S = (A Bm^T) * M ----
+            float acc[RI][RI];
+#pragma unroll
+            for (int i = 0; i < RI; ++i)
+#pragma unroll
+                for (int j = 0; j < RI; ++j) acc[i][j] = 0.f;
+            for (int k = 0; k < D; ++k) {
+                float av[RI], bv[RI];
+#pragma unroll
+                for (int i = 0; i < RI; ++i) av[i] = sA[(ty + 16 * i) * LD + k];
+#pragma unroll
+                for (int j = 0; j < RI; ++j) bv[j] = sB[(tx + 16 * j) * LD + k];
+#pragma unroll
+                for (int i = 0; i < RI; ++i)
+#pragma unroll
+                    for (int j = 0; j < RI; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+            }
+#pragma unroll
+            for (int i = 0; i < RI; ++i)
+#pragma unroll
+                for (int j = 0; j < RI; ++j) {
+                    int r = ty + 16 * i, c = tx + 16 * j;
+                    float m;
+                    if (!REV) m = (r >= c) ? sPw[r - c] : 0.f;
+                    else      m = (c >= r) ? sPw[c - r] : 0.f;
+                    sS[r * LS + c] = acc[i][j] * m;
+                }
+            __syncthreads();
+
+            // ---- Out = S C + rowscale * (A St) ----
+            float oi[RI][CJ], ox[RI][CJ];
+#pragma unroll
+            for (int i = 0; i < RI; ++i)
+#pragma unroll
+                for (int j = 0; j < CJ; ++j) { oi[i][j] = 0.f; ox[i][j] = 0.f; }
+            for (int c = 0; c < BK; ++c) {
+                float sv[RI], cv[CJ];
+#pragma unroll
+                for (int i = 0; i < RI; ++i) sv[i] = sS[(ty + 16 * i) * LS + c];
+#pragma unroll
+                for (int j = 0; j < CJ; ++j) cv[j] = sC[c * LD + tx + 16 * j];
+#pragma unroll
+                for (int i = 0; i < RI; ++i)
+#pragma unroll
+                    for (int j = 0; j < CJ; ++j) oi[i][j] = fmaf(sv[i], cv[j], oi[i][j]);
+            }
+            for (int k = 0; k < D; ++k) {
+                float av[RI], sv[CJ];
+#pragma unroll
+                for (int i = 0; i < RI; ++i) av[i] = sA[(ty + 16 * i) * LD + k];
+#pragma unroll
+                for (int j = 0; j < CJ; ++j) sv[j] = sKV[k * LD + tx + 16 * j];
+#pragma unroll
+                for (int i = 0; i < RI; ++i)
+#pragma unroll
+                    for (int j = 0; j < CJ; ++j) ox[i][j] = fmaf(av[i], sv[j], ox[i][j]);
+            }
+#pragma unroll
+            for (int i = 0; i < RI; ++i) {
+                int r = ty + 16 * i;
+                int t = t0 + r;
+                float rs = REV ? sPw[BK - r] : sPw[r + 1];
+                if (t < seg_hi) {
+#pragma unroll
+                    for (int j = 0; j < CJ; ++j)
+                        gO[(size_t)t * D + tx + 16 * j] = fmaf(rs, ox[i][j], oi[i][j]);
+                }
+            }
+            __syncthreads();   // everyone is done reading the old state
+        }
+
+        // ---- St <- lambda^BK St + sum_r w_r Bm[r] C[r]^T ----
+        {
+            float up[CJ][CJ];
+#pragma unroll
+            for (int i = 0; i < CJ; ++i)
+#pragma unroll
+                for (int j = 0; j < CJ; ++j) up[i][j] = 0.f;
+            for (int r = 0; r < BK; ++r) {
+                float w = REV ? sPw[r] : sPw[BK - 1 - r];
+                float bv[CJ], cv[CJ];
+#pragma unroll
+                for (int i = 0; i < CJ; ++i) bv[i] = w * sB[r * LD + ty + 16 * i];
+#pragma unroll
+                for (int j = 0; j < CJ; ++j) cv[j] = sC[r * LD + tx + 16 * j];
+#pragma unroll
+                for (int i = 0; i < CJ; ++i)
+#pragma unroll
+                    for (int j = 0; j < CJ; ++j) up[i][j] = fmaf(bv[i], cv[j], up[i][j]);
+            }
+#pragma unroll
+            for (int i = 0; i < CJ; ++i)
+#pragma unroll
+                for (int j = 0; j < CJ; ++j) {
+                    float *p = sKV + (ty + 16 * i) * LD + tx + 16 * j;
+                    *p = fmaf(lamBK, *p, up[i][j]);
+                }
+        }
+        __syncthreads();
+    }
+
+    if (STATE_ONLY) {
+        for (int e = tid; e < D * D; e += 256) {
+            int i = e / D, j = e % D;
+            gSt[e] = sKV[i * LD + j];
+        }
+    }
+}
+
+// In-place exclusive scan of the segment states of each (batch, head):
+// forward  P_0 = 0, P_{s+1} = lambda^L P_s + S_s     (App. C, KV_t at segment granularity)
+// reverse  D_{S-1} = 0, D_{s-1} = lambda^L D_s + S_s (App. C, dKV_t likewise)
+template <bool REV>
+__global__ __launch_bounds__(256) void la_segment_scan(SegScanArgs a, LaLambdas lams)
+{
+    const int scan = blockIdx.y;
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= a.DD) return;
+    const float lam = lams.v[scan % a.H];
+    const float lamL = (float)pow((double)lam, (double)a.L);
+    float *W = a.states + (size_t)scan * a.S * a.DD + e;
+    float carry = 0.f;
+    for (int i = 0; i < a.S; ++i) {
+        const int s = REV ? (a.S - 1 - i) : i;
+        const bool last = (i == a.S - 1);
+        // the final segment's own local state was not produced and is not needed
+        float loc = last ? 0.f : W[(size_t)s * a.DD];
+        W[(size_t)s * a.DD] = carry;
+        carry = fmaf(lamL, carry, loc);
+    }
+}

@@ -1,0 +1,92 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol include/la.h declares, plans deterministically and rejects bad
+arguments before enqueuing anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2405_17381_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "la.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(la_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load_library()
+    names = _declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_strerror_is_distinct_per_status():
+    msgs = {binding.la_strerror(s) for s in range(0, -8, -1)}
+    assert len(msgs) == 8
+    assert binding.la_strerror(-99) == "unknown status"
+
+
+def test_plan_and_workspace(monkeypatch):
+    monkeypatch.delenv("LA_LSEG", raising=False)
+    # many scans: one segment, no scratch
+    tile, L, S = binding.la_plan(32, 16, 2048, 128, binding.LA_BF16)
+    assert (tile, S) == (64, 1) and L >= 2048
+    assert binding.la_workspace_bytes(32, 16, 2048, 128, binding.LA_BF16, False) == 0
+    # few scans, long sequence: segmented, scratch = scans * S * d*d * 4
+    tile, L, S = binding.la_plan(1, 16, 65536, 128, binding.LA_BF16)
+    assert S > 1 and L % tile == 0 and (S - 1) * L < 65536 <= S * L
+    need = binding.la_workspace_bytes(1, 16, 65536, 128, binding.LA_BF16, True)
+    assert need == 16 * S * 128 * 128 * 4
+    # fp32 tile lengths
+    assert binding.la_plan(1, 2, 256, 64, binding.LA_F32)[0] == 64
+    assert binding.la_plan(1, 2, 256, 128, binding.LA_F32)[0] == 32
+    # override
+    monkeypatch.setenv("LA_LSEG", "128")
+    assert binding.la_plan(1, 2, 300, 64, binding.LA_BF16) == (64, 128, 3)
+    # invalid problem: no scratch, error status from the plan
+    assert binding.la_workspace_bytes(1, 1, 16, 96, binding.LA_BF16, False) == 0
+    with pytest.raises(binding.LaError):
+        binding.la_plan(1, 1, 16, 96, binding.LA_BF16)
+
+
+def _raw_fwd(Q=4096, K=4096, V=4096, lam=(0.5,), O=4096, B=1, H=1, n=8, d=64, dt=1, ws=0, wsb=0):
+    lib = binding.load_library()
+    lam_arr = (ctypes.c_float * max(1, len(lam)))(*lam) if lam is not None else None
+    return lib.la_fwd(Q, K, V, lam_arr, O, B, H, n, d, dt, ws, wsb, None)
+
+
+def test_bad_arguments_are_rejected_without_a_gpu(monkeypatch):
+    """Every rejection happens before any HIP call, so fake (never
+    dereferenced) pointers are enough to drive the checks."""
+    monkeypatch.delenv("LA_LSEG", raising=False)
+    assert _raw_fwd(d=96) == -2
+    assert _raw_fwd(n=0) == -2
+    assert _raw_fwd(H=257, lam=(0.5,) * 257) == -2
+    assert _raw_fwd(dt=7) == -3
+    assert _raw_fwd(Q=0) == -1
+    assert _raw_fwd(lam=None) == -1
+    assert _raw_fwd(Q=4100) == -7
+    for bad in (0.0, -0.1, 1.5, float("nan"), float("inf")):
+        assert _raw_fwd(lam=(bad,)) == -4
+    # segmented plan without scratch
+    monkeypatch.setenv("LA_LSEG", "64")
+    assert _raw_fwd(n=256, ws=0, wsb=0) == -5
+    assert _raw_fwd(n=256, ws=4096 + 8, wsb=1 << 30) == -5      # misaligned
+    assert _raw_fwd(n=256, ws=4096, wsb=16) == -5               # too small
+    lib = binding.load_library()
+    lam_arr = (ctypes.c_float * 1)(0.5)
+    assert lib.la_bwd(4096, 4096, 4096, lam_arr, 4096, 4096, 4096, 0,
+                      1, 1, 8, 64, 1, 0, 0, None) == -1
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 1, 8, 64)
+    with pytest.raises(ValueError):
+        binding.la_fwd(x, x, x, [0.5])

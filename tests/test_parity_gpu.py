@@ -1,0 +1,225 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle,
+element by element, on the same seeded inputs.
+
+Tolerances (max|x - ref| / max|ref| per output tensor):
+  fp32 path  <= 1e-4        bf16 path  <= 2e-2 on O and on every gradient.
+For bf16 the oracle consumes the bf16-rounded inputs in fp64, so the measured
+error is the kernels' internal rounding only.
+"""
+import os
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2405_17381_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(autouse=True)
+def _need_gpu_and_clean_env(monkeypatch):
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load_library()                      # fail loudly if the HIP library is missing
+    monkeypatch.delenv("LA_LSEG", raising=False)
+    yield
+    torch.cuda.synchronize()
+
+
+def _to_dev(xs, dtype):
+    return [x.to(TDT[dtype]).cuda().contiguous() for x in xs]
+
+
+def _ref_inputs(xs, dtype):
+    """What the GPU actually sees, widened to fp64."""
+    return [x.to(TDT[dtype]).to(torch.float64).numpy() for x in xs]
+
+
+def _run_gpu(w, xs, lseg=None):
+    if lseg is not None:
+        os.environ["LA_LSEG"] = str(lseg)
+    try:
+        Q, K, V, dO = _to_dev(xs, w.dtype)
+        O = binding.la_fwd(Q, K, V, w.lambdas)
+        dQ, dK, dV = binding.la_bwd(Q, K, V, w.lambdas, dO)
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("LA_LSEG", None)
+    return [t.to(torch.float64).cpu().numpy() for t in (O, dQ, dK, dV)]
+
+
+def _compare(w, got, ref, tol, label):
+    names = ("O", "dQ", "dK", "dV")
+    worst = 0.0
+    for nm, x, r in zip(names, got, ref):
+        assert np.all(np.isfinite(x)), (label, nm, "non-finite output")
+        err = oracle.rel_max_err(x, r)
+        worst = max(worst, err)
+        # per-head error: heads differ in lambda
+        for h in range(r.shape[1]):
+            eh = oracle.rel_max_err(x[:, h], r[:, h])
+            assert eh <= 2 * tol, (label, nm, "head", h, eh)
+        assert err <= tol, (label, nm, err)
+    _say("  %s: worst rel err %.3e (tol %.0e)" % (label, worst, tol))
+    return worst
+
+
+def _full_case(w, lseg=None, use_left_product=False):
+    label = "%s B%d H%d n%d d%d %s lseg=%s" % (w.name, w.B, w.H, w.n, w.d, w.dtype, lseg)
+    _say("case " + label)
+    xs = synth.draw(w)
+    got = _run_gpu(w, xs, lseg)
+    q, k, v, g = _ref_inputs(xs, w.dtype)
+    if use_left_product:
+        ref = (oracle.left_product_fwd(q, k, v, w.lambdas),) + oracle.left_product_bwd(q, k, v, w.lambdas, g)
+    else:
+        ref = (oracle.c_recurrence_fwd(q, k, v, w.lambdas),) + oracle.c_recurrence_bwd(q, k, v, w.lambdas, g)
+    return _compare(w, got, ref, TOL[w.dtype], label)
+
+
+# ---- configs[0]: fp32, B=1 H=2 n=256 d=64, lambda = (1.0, 0.99), block size 64 ------
+def test_c1_fp32_against_both_oracle_forms():
+    w = synth.workload("c1")
+    assert binding.la_plan(w.B, w.H, w.n, w.d, binding.LA_F32)[0] == 64
+    _full_case(w)
+    _full_case(w, use_left_product=True)
+    _full_case(w, lseg=64)          # four segments of one block each
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("n,lseg", [(1, None), (63, None), (200, None), (333, 128), (512, 64)])
+def test_fp32_ragged_and_segmented(d, n, lseg):
+    lam = [1.0, 0.99, 0.5, 0.05, 1e-6]
+    w = synth.custom(2, len(lam), n, d, lam, seed=1000 + n + d, dtype="f32")
+    _full_case(w, lseg)
+
+
+# ---- bf16 ----------------------------------------------------------------------------
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("n,lseg", [(1, None), (64, None), (65, None), (300, None), (1000, None),
+                                    (640, 128), (1000, 256), (1337, 64)])
+def test_bf16_ragged_and_segmented(d, n, lseg):
+    lam = [1.0, 0.9999, 0.95, 0.6, 0.05, 1e-6]
+    w = synth.custom(2, len(lam), n, d, lam, seed=2000 + n + d, dtype="bf16")
+    _full_case(w, lseg)
+
+
+def test_c2_bf16_d64_full():
+    _full_case(synth.workload("c2"))
+    _full_case(synth.workload("c2"), lseg=512)
+
+
+def test_result_independent_of_segmentation_bf16():
+    """The block recurrence (App. C) makes the result independent of where
+    the sequence is cut; on the GPU only the rounding may move."""
+    lam = [1.0, 0.999, 0.9]
+    w = synth.custom(1, 3, 2048, 128, lam, seed=77, dtype="bf16")
+    xs = synth.draw(w)
+    base = _run_gpu(w, xs, lseg=None)
+    for lseg in (64, 512, 1024):
+        other = _run_gpu(w, xs, lseg=lseg)
+        for a, b in zip(base, other):
+            assert oracle.rel_max_err(b, a) <= 1e-2, lseg
+
+
+def test_bitwise_reproducible():
+    w = synth.custom(2, 4, 1500, 128, [1.0, 0.99, 0.9, 0.5], seed=5, dtype="bf16")
+    xs = synth.draw(w)
+    a = _run_gpu(w, xs, lseg=256)
+    b = _run_gpu(w, xs, lseg=256)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+def test_outputs_are_fully_overwritten_and_neighbours_untouched():
+    """Canaries: outputs pre-filled with NaN come back finite everywhere, and
+    guard rows placed before and after each output buffer stay intact."""
+    w = synth.custom(1, 2, 333, 128, [1.0, 0.97], seed=9, dtype="bf16")
+    Q, K, V, dO = _to_dev(synth.draw(w), "bf16")
+    n_el = Q.numel()
+    guard = 4096
+    bufs = []
+    for _ in range(4):
+        big = torch.full((n_el + 2 * guard,), float("nan"), dtype=torch.bfloat16, device="cuda")
+        big[:guard] = 123.0
+        big[-guard:] = 123.0
+        bufs.append(big)
+    outs = [b[guard:guard + n_el].view_as(Q) for b in bufs]
+    binding.la_fwd(Q, K, V, w.lambdas, O=outs[0])
+    binding.la_bwd(Q, K, V, w.lambdas, dO, dQ=outs[1], dK=outs[2], dV=outs[3])
+    torch.cuda.synchronize()
+    for big, o in zip(bufs, outs):
+        assert torch.isfinite(o.float()).all()
+        assert (big[:guard] == 123.0).all() and (big[-guard:] == 123.0).all()
+
+
+# ---- full-size configs, in the launch configuration the benchmark times -----------------
+def _sampled_case(w, sample, slabwise=False):
+    """Run the whole workload on the GPU; compare the complete scans of the
+    sampled (b, h) pairs with the oracle; check the trilinearity invariant
+    <dO,O> = <dQ,Q> = <dK,K> = <dV,V> over the entire tensors."""
+    label = "%s B%d H%d n%d d%d" % (w.name, w.B, w.H, w.n, w.d)
+    _say("case %s (sampled scans %s)" % (label, sample))
+    t0 = time.time()
+    dt = TDT[w.dtype]
+    if slabwise:
+        Q, K, V, dO = synth.draw_slabwise(w, device="cuda", dtype=dt)
+        host = None
+    else:
+        host = synth.draw(w)
+        Q, K, V, dO = _to_dev(host, w.dtype)
+    _say("  inputs ready in %.1fs" % (time.time() - t0))
+    O = binding.la_fwd(Q, K, V, w.lambdas)
+    dQ, dK, dV = binding.la_bwd(Q, K, V, w.lambdas, dO)
+    torch.cuda.synchronize()
+    _say("  plan (tile, L, S) = %s" % (binding.la_plan(w.B, w.H, w.n, w.d, binding.LA_BF16),))
+    for t in (O, dQ, dK, dV):
+        assert torch.isfinite(t.float()).all()
+    worst = 0.0
+    for (b, h) in sample:
+        ins = [x[b, h].to(torch.float64).cpu().numpy()[None, None] for x in (Q, K, V, dO)]
+        lam = [w.lambdas[h]]
+        ref = (oracle.c_recurrence_fwd(ins[0], ins[1], ins[2], lam),) + \
+            oracle.c_recurrence_bwd(ins[0], ins[1], ins[2], lam, ins[3])
+        for nm, x, r in zip(("O", "dQ", "dK", "dV"), (O, dQ, dK, dV), ref):
+            got = x[b, h].to(torch.float64).cpu().numpy()[None, None]
+            err = oracle.rel_max_err(got, r)
+            worst = max(worst, err)
+            assert err <= TOL[w.dtype], (label, b, h, nm, err)
+        _say("  scan (b=%d,h=%d, lambda=%.6f) ok, worst so far %.3e  [%.1fs]"
+             % (b, h, w.lambdas[h], worst, time.time() - t0))
+    # trilinearity over everything, per head, accumulated in fp64 on the device
+    def inner(x, y):
+        return (x.double() * y.double()).sum(dim=(0, 2, 3))
+    base = inner(dO, O)
+    for nm, gx, x in (("dQ", dQ, Q), ("dK", dK, K), ("dV", dV, V)):
+        rel = ((inner(gx, x) - base).abs() / base.abs().clamp_min(1e-30)).max().item()
+        assert rel <= 2e-2, (label, nm, rel)
+    _say("  trilinearity ok")
+
+
+@pytest.mark.parametrize("n", [2048, 4096, 8192, 16384, 32768, 65536])
+def test_c3_sweep_point_sampled(n):
+    w = synth.workload("c3_%d" % n)
+    sample = [(0, 0), (w.B - 1, 15)] if n <= 16384 else [(0, 15)]
+    _sampled_case(w, sample)
+
+
+def test_c4_silu_features_sampled():
+    _sampled_case(synth.workload("c4"), [(0, 0), (7, 31), (3, 17)])
+
+
+def test_c5_long_context_sampled():
+    # heads with lambda = 1 (no decay over 2048 blocks) and the slowest decay
+    _sampled_case(synth.workload("c5"), [(0, 0), (0, 31)], slabwise=True)
