@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark: Lightning Attention fwd+bwd tokens/s on one MI355X.
+
+Workload (`config.workload`): the bf16 sequence-length sweep at a fixed 65 536
+tokens per batch, H=16, d=128, (B, n) in {(32,2K) ... (1,64K)}, per-head decay
+geometric in [0.9, 0.9999].  One "step" is one forward + one backward pass of
+the whole hot path at each of the six sweep points; `value` is total tokens
+per second over the timed steps, with inputs resident in HBM.
+
+Besides the headline the JSON line carries per-point figures (`sweep`), the
+roofline of the dominant kernel (`roofline`) and the CPU oracle timed on the
+host cores (`cpu_baseline`).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+H, D, TOKENS = 16, 128, 65536
+POINTS = [(32, 2048), (16, 4096), (8, 8192), (4, 16384), (2, 32768), (1, 65536)]
+# model flops per token per head, fwd + bwd, Alg. 5/6 at block length = d: 8d^2 + 22d^2
+MODEL_FLOPS_PER_TOKEN_HEAD = 30 * D * D
+
+
+def read_traffic_note():
+    """HBM bytes per launch of the dominant kernel measured with rocprofv3
+    --pmc (FETCH_SIZE, WRITE_SIZE), if a summary has been committed."""
+    path = os.path.join(ROOT, "profiles", "scan_bf16_d128_c3_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1].strip())
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline():
+    """The CPU oracle (compiled token recurrence, fp64, OpenMP over scans), as
+    it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    from paper_2405_17381_amd import synth
+    w = synth.workload("c3_65536")
+    n = w.n
+    rng = np.random.default_rng(w.seed)
+    xs = [(rng.standard_normal((1, H, n, D), dtype=np.float32) / np.sqrt(D)).astype(np.float64)
+          for _ in range(4)]
+    threads = oracle.oracle_threads()
+    t0 = time.perf_counter()
+    oracle.c_recurrence_fwd(xs[0], xs[1], xs[2], w.lambdas)
+    oracle.c_recurrence_bwd(xs[0], xs[1], xs[2], w.lambdas, xs[3])
+    dt = time.perf_counter() - t0
+    return {
+        "value": n / dt, "unit": "tokens/s", "cores": min(threads, H), "kind": "oracle",
+        "sample": "the whole (B=1, n=65536) sweep point (one batch of 65536 tokens), all 16 heads, "
+                  "d=128, fwd+bwd token recurrence in fp64; %.1f s wall on %d OpenMP threads "
+                  "(one thread per head)" % (dt, threads),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the hot path is a single-GPU kernel "
+              "library; no collectives). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2405_17381_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    binding.load_library()
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    lam = synth.workload("c3_2048").lambdas
+
+    numel = TOKENS * H * D
+    gen = torch.Generator(device=dev).manual_seed(synth.BASE_SEED + 3)
+    scale = 1.0 / (D ** 0.5)
+    flat = {}
+    for name in ("Q", "K", "V"):
+        flat[name] = (torch.randn(numel, generator=gen, device=dev, dtype=torch.float32) * scale).to(torch.bfloat16)
+    flat["dO"] = torch.randn(numel, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    for name in ("O", "dQ", "dK", "dV"):
+        flat[name] = torch.empty(numel, device=dev, dtype=torch.bfloat16)
+    ws_bytes = max(binding.la_workspace_bytes(B, H, n, D, binding.LA_BF16, True) for B, n in POINTS)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+
+    def views(B, n):
+        return {k: v.view(B, H, n, D) for k, v in flat.items()}
+
+    def fwd_bwd(B, n):
+        t = views(B, n)
+        binding.la_fwd(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=ws)
+        binding.la_bwd(t["Q"], t["K"], t["V"], lam, t["dO"], dQ=t["dQ"], dK=t["dK"], dV=t["dV"], workspace=ws)
+
+    def step():
+        for B, n in POINTS:
+            fwd_bwd(B, n)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    tokens_per_step = TOKENS * len(POINTS)
+    value = tokens_per_step * args.steps / elapsed
+
+    # ---- per sweep point (events on the stream the kernels run on) -------------
+    sweep = []
+    for B, n in POINTS:
+        t = views(B, n)
+        times = {}
+        for what in ("fwd", "bwd"):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(args.steps):
+                if what == "fwd":
+                    binding.la_fwd(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=ws)
+                else:
+                    binding.la_bwd(t["Q"], t["K"], t["V"], lam, t["dO"], dQ=t["dQ"], dK=t["dK"],
+                                   dV=t["dV"], workspace=ws)
+            e1.record()
+            e1.synchronize()
+            times[what] = e0.elapsed_time(e1) / args.steps
+        tot_ms = times["fwd"] + times["bwd"]
+        tps = TOKENS / (tot_ms * 1e-3)
+        tflops = tps * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12
+        _, L, S = binding.la_plan(B, H, n, D, binding.LA_BF16)
+        sweep.append({"B": B, "n": n, "fwd_ms": round(times["fwd"], 4), "bwd_ms": round(times["bwd"], 4),
+                      "tokens_per_s": round(tps, 1), "model_tflops": round(tflops, 2),
+                      "pct_mfma_bf16_peak": round(100.0 * tflops / MFMA_BF16_PEAK_TFLOPS, 2),
+                      "segment_len": L, "segments": S})
+
+    # ---- roofline of the dominant kernel: the block-scan kernel -------------------
+    # One launch streams three [tokens, H, d] bf16 operands in and one out:
+    # 4 * 2 * d bytes per token per head.
+    binding.la_profile_enable(True)
+    binding.la_profile_collect()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    scan_ms, launches = binding.la_profile_collect()
+    binding.la_profile_enable(False)
+    alg_bytes_per_launch = 4 * 2 * D * H * TOKENS
+    avg_ms = scan_ms / max(launches, 1)
+    achieved = alg_bytes_per_launch / (avg_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "la_scan_bf16<128>", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": read_traffic_note(), "launches": launches,
+                "avg_launch_ms": round(avg_ms, 5), "algorithmic_bytes_per_launch": alg_bytes_per_launch}
+
+    total_tflops = value * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12
+    out = {
+        "metric": "fwd+bwd tokens/s (causal linear attention with decay, bf16, d=128, seq-len sweep "
+                  "2K-64K at 64K tokens per batch)",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c3 sweep: (B,n) in {(32,2048),(16,4096),(8,8192),(4,16384),(2,32768),"
+                               "(1,65536)}, H=16, d=128, lambda_h geometric in [0.9,0.9999]; one step = "
+                               "fwd+bwd at all six points (393216 tokens)",
+                   "tokens_per_step": tokens_per_step, "H": H, "d": D},
+        "model_tflops": round(total_tflops, 2),
+        "pct_mfma_bf16_peak": round(100.0 * total_tflops / MFMA_BF16_PEAK_TFLOPS, 2),
+        "sweep": sweep,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
