@@ -72,7 +72,16 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--point", type=int, default=0,
+                    help="profiling aid: restrict the step to the sweep point with this n")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="profiling aid: also run a plain 256 MiB -> 256 MiB device copy per step, "
+                         "whose FETCH_SIZE / WRITE_SIZE readings calibrate the HBM counters")
     args = ap.parse_args()
+    global POINTS
+    if args.point:
+        POINTS = [(B, n) for (B, n) in POINTS if n == args.point]
+        assert POINTS, "no sweep point with n=%d" % args.point
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the hot path is a single-GPU kernel "
               "library; no collectives). Re-run with --gpus 1.", file=sys.stderr)
@@ -110,6 +119,8 @@ def main():
     def step():
         for B, n in POINTS:
             fwd_bwd(B, n)
+        if args.calib_copy:
+            flat["O"].copy_(flat["Q"])
 
     for _ in range(args.warmup):
         step()
@@ -175,7 +186,8 @@ def main():
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "c3 sweep: (B,n) in {(32,2048),(16,4096),(8,8192),(4,16384),(2,32768),"
+        "config": {"workload": ("" if not args.point else "PROFILING SUBSET n=%d of: " % args.point) +
+                               "c3 sweep: (B,n) in {(32,2048),(16,4096),(8,8192),(4,16384),(2,32768),"
                                "(1,65536)}, H=16, d=128, lambda_h geometric in [0.9,0.9999]; one step = "
                                "fwd+bwd at all six points (393216 tokens)",
                    "tokens_per_step": tokens_per_step, "H": H, "d": D},

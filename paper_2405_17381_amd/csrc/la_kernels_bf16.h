@@ -4,23 +4,31 @@
 // segment of one (batch, head) scan.  All four contractions of a block run on
 // v_mfma_f32_32x32x16_bf16 with fp32 accumulation:
 //
-//   S^T = Bm A^T           (scores, transposed; contraction over the feature dim)
-//   Out = P C              (intra block, P = bf16(S * decay mask))
-//   Out+= rowscale * A St  (inter block, against the running state)
-//   St  = lambda^BK St + (w * Bm)^T C
+//   S^T   = Bm A^T              scores, transposed; contraction over the feature dim
+//   Out^T = C^T P^T             intra block, P = bf16(S * decay mask)
+//   Out^T+= (St^T A^T) * scale  inter block, against the running state
+//   St    = lambda^BK St + (w * Bm)^T C
 //
 // Ownership.  Wave w owns the value-feature slice j in [32w, 32w+32): its
 // columns of Out and of the state St[:, slice].  The state never leaves the
 // wave's accumulator registers: the fp32 accumulator layout of a 32x32 tile
-// (lane = column, registers = rows) is exactly an MFMA B operand with a
+// (lane = column j, registers = rows i) is exactly an MFMA operand with a
 // permuted contraction order, so it is rounded to bf16 in registers and fed
-// straight back; the A operand (rows of the A tile in LDS) is read with the
-// same permutation.
+// straight back as the A operand of Out^T = St^T A^T; the rows of the A tile
+// are stored in LDS with the matching column permutation, so that both this
+// product and the score product read them with 16-byte loads.
 //
-// LDS tiles per block: A and Bm row-major (for the feature-dim contraction),
-// C^T and (w*Bm)^T transposed (for the token-dim contractions; the transpose
-// is done in registers while staging), P row-major, and the Out tile reuses
-// A's storage so that global stores are full 16-byte rows.
+// LDS tiles per block
+//   sA, sB   A and Bm row-major [row][feature'], feature' = feature with the two
+//            middle quads of every 16 swapped (see above), row stride D+8
+//   sBT,sCT  (w*Bm)^T and C^T, [feature][row], transposed in registers while
+//            staging; 128-byte rows, XOR-swizzled so that both the 8-byte
+//            transposing stores and the 16-byte operand loads are conflict free
+//   sP       masked scores [q][key], row stride 72
+//   sO       the Out tile, staged as bf16 in sB's storage (free once the scores
+//            are done) with sB's layout, so every thread later overwrites, when
+//            staging the next block, exactly the bytes it read itself: no
+//            barrier is needed between the two.
 //
 // MFMA 32x32x16 bf16 register layout used throughout (lane l, i = l % 32,
 // g = l / 32):  A operand: row i, k = 8g + e (e = 0..7);  B operand: column i,
@@ -32,7 +40,6 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
-
 typedef uint32_t U4 __attribute__((ext_vector_type(4)));   // 16 bytes = 8 bf16
 typedef uint32_t U2 __attribute__((ext_vector_type(2)));   //  8 bytes = 4 bf16
 
@@ -44,6 +51,9 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi)
 }
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// (lo half of a, lo half of b) and (hi half of a, hi half of b) as one dword
+__device__ __forceinline__ uint32_t pair_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t pair_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 
 __device__ __forceinline__ f32x16_t mfma32(const U4 &a, const U4 &b, f32x16_t c)
 {
@@ -51,15 +61,21 @@ __device__ __forceinline__ f32x16_t mfma32(const U4 &a, const U4 &b, f32x16_t c)
                                                    __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
+// Transposed-tile addressing, in bf16 elements: feature f (row), block row r.
+//   physical row   = f with bits 0 and 3 swapped (so that the 16 features 8*sc+e
+//                    written by one store instruction fall on both bank halves)
+//   16-byte chunk  = (r / 8) ^ phi(f),  phi(f) = (f & 7) ^ ((f >> 4) & 7)
+__device__ __forceinline__ int tt_row(int f) { return (f & ~9) | ((f & 1) << 3) | ((f >> 3) & 1); }
+__device__ __forceinline__ int tt_phi(int f) { return (f & 7) ^ ((f >> 4) & 7); }
+
 template <int D>
 struct Bf16Cfg {
     static constexpr int BK = 64;
     static constexpr int NW = D / 32;          // wavefronts per workgroup
     static constexpr int NT = NW * 64;
     static constexpr int LDN = D + 8;          // row stride of row-major tiles (elements)
-    static constexpr int LDT = BK + 8;         // row stride of transposed tiles
     static constexpr int LDP = BK + 8;
-    static constexpr int nA = BK * LDN, nB = BK * LDN, nBT = D * LDT, nCT = D * LDT, nP = BK * LDP;
+    static constexpr int nA = BK * LDN, nB = BK * LDN, nBT = D * BK, nCT = D * BK, nP = BK * LDP;
     static constexpr size_t lds_bytes = 2 * (size_t)(nA + nB + nBT + nCT + nP);
 };
 
@@ -67,8 +83,8 @@ template <int D, bool REV, bool STATE_ONLY>
 __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas lams)
 {
     using Cfg = Bf16Cfg<D>;
-    constexpr int BK = Cfg::BK, NW = Cfg::NW, NT = Cfg::NT;
-    constexpr int LDN = Cfg::LDN, LDT = Cfg::LDT, LDP = Cfg::LDP;
+    constexpr int BK = Cfg::BK, NW = Cfg::NW;
+    constexpr int LDN = Cfg::LDN, LDP = Cfg::LDP;
     constexpr int KS_D = D / 16;               // k-steps over the feature dim
     constexpr int KS_B = BK / 16;              // k-steps over the block rows (= 4)
     constexpr int MT_D = D / 32;               // 32-row tiles over the feature dim
@@ -81,6 +97,7 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
     uint16_t *sBT = sB + Cfg::nB;
     uint16_t *sCT = sBT + Cfg::nBT;
     uint16_t *sP = sCT + Cfg::nCT;
+    uint16_t *sO = sB;
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63, l32 = l & 31, g = l >> 5;
@@ -114,17 +131,32 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
         wst[i] = REV ? pw(r) : pw(BK - 1 - r);
     }
     const float lamBK = pw(BK);
-    float rs16[16];                            // inter-block row scale inside a 32-row tile
-    float rs_tile[2];
+    // row-major tiles: this thread's two 8-byte pieces of chunk sc
+    const int nat_off = 16 * (sc >> 1) + 4 * (sc & 1);
+    // transposed tiles: element offsets of this thread's 8 stores (feature 8sc+e)
+    int tw_off[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int f = 8 * sc + e;
+        tw_off[e] = tt_row(f) * BK + 8 * ((sa >> 1) ^ tt_phi(f)) + 4 * (sa & 1);
+    }
+    // transposed tiles: operand rows read by this lane
+    const int ct_row = tt_row(32 * w + l32) * BK, ct_phi = tt_phi(32 * w + l32);
+    int bt_row[MT_D], bt_phi[MT_D];
+#pragma unroll
+    for (int mt = 0; mt < MT_D; ++mt) {
+        bt_row[mt] = tt_row(32 * mt + l32) * BK;
+        bt_phi[mt] = tt_phi(32 * mt + l32);
+    }
+
+    float rsq[2];                              // inter-block scale of column q = 32mt + l32
     float mk[NTILE][16];                       // decay mask of this wave's score tiles
     if (!STATE_ONLY) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            int ql = 8 * (v >> 2) + 4 * g + (v & 3);
-            rs16[v] = REV ? pw(32 - ql) : pw(ql + 1);
+        for (int mt = 0; mt < 2; ++mt) {
+            const int q = 32 * mt + l32;
+            rsq[mt] = REV ? pw(BK - q) : pw(q + 1);
         }
-        rs_tile[0] = REV ? pw(32) : 1.0f;
-        rs_tile[1] = REV ? 1.0f : pw(32);
 #pragma unroll
         for (int ti = 0; ti < NTILE; ++ti) {
             int tile = w + ti * NW;            // 0,1,2 -> (kt,qt)
@@ -150,7 +182,7 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
             int i = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
             st[mt][v] = has_init ? gSt[(size_t)i * D + 32 * w + l32] : 0.0f;
         }
-    U4 sf[KS_D];                               // bf16 copy of the state as MFMA B operand
+    U4 sf[KS_D];                               // bf16 copy of the state as an MFMA operand
     auto refresh_state_operand = [&]() {
 #pragma unroll
         for (int ks = 0; ks < KS_D; ++ks) {
@@ -188,33 +220,35 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
         if (!STATE_ONLY) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                *(U4 *)(sA + (4 * sa + i) * LDN + 8 * sc) = ra[i];
-                *(U4 *)(sB + (4 * sa + i) * LDN + 8 * sc) = rb[i];
+                uint16_t *pa = sA + (4 * sa + i) * LDN + nat_off;
+                uint16_t *pb = sB + (4 * sa + i) * LDN + nat_off;
+                *(U2 *)(pa) = U2{ra[i][0], ra[i][1]};
+                *(U2 *)(pa + 8) = U2{ra[i][2], ra[i][3]};
+                *(U2 *)(pb) = U2{rb[i][0], rb[i][1]};
+                *(U2 *)(pb + 8) = U2{rb[i][2], rb[i][3]};
             }
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             // element e of each of the 4 rows -> 4 consecutive block rows of feature 8sc+e
+            const int j = e >> 1;
             float b0, b1, b2, b3;
-            uint32_t c0, c1, c2, c3;
-            if (e & 1) {
-                b0 = bf16_hi(rb[0][e >> 1]); b1 = bf16_hi(rb[1][e >> 1]);
-                b2 = bf16_hi(rb[2][e >> 1]); b3 = bf16_hi(rb[3][e >> 1]);
-                c0 = rc[0][e >> 1] >> 16; c1 = rc[1][e >> 1] >> 16;
-                c2 = rc[2][e >> 1] >> 16; c3 = rc[3][e >> 1] >> 16;
-            } else {
-                b0 = bf16_lo(rb[0][e >> 1]); b1 = bf16_lo(rb[1][e >> 1]);
-                b2 = bf16_lo(rb[2][e >> 1]); b3 = bf16_lo(rb[3][e >> 1]);
-                c0 = rc[0][e >> 1] & 0xffffu; c1 = rc[1][e >> 1] & 0xffffu;
-                c2 = rc[2][e >> 1] & 0xffffu; c3 = rc[3][e >> 1] & 0xffffu;
-            }
             U2 tb, tc;
+            if (e & 1) {
+                b0 = bf16_hi(rb[0][j]); b1 = bf16_hi(rb[1][j]);
+                b2 = bf16_hi(rb[2][j]); b3 = bf16_hi(rb[3][j]);
+                tc[0] = pair_hi(rc[0][j], rc[1][j]);
+                tc[1] = pair_hi(rc[2][j], rc[3][j]);
+            } else {
+                b0 = bf16_lo(rb[0][j]); b1 = bf16_lo(rb[1][j]);
+                b2 = bf16_lo(rb[2][j]); b3 = bf16_lo(rb[3][j]);
+                tc[0] = pair_lo(rc[0][j], rc[1][j]);
+                tc[1] = pair_lo(rc[2][j], rc[3][j]);
+            }
             tb[0] = pack2_bf16(b0 * wst[0], b1 * wst[1]);
             tb[1] = pack2_bf16(b2 * wst[2], b3 * wst[3]);
-            tc[0] = c0 | (c1 << 16);
-            tc[1] = c2 | (c3 << 16);
-            *(U2 *)(sBT + (8 * sc + e) * LDT + 4 * sa) = tb;
-            *(U2 *)(sCT + (8 * sc + e) * LDT + 4 * sa) = tc;
+            *(U2 *)(sBT + tw_off[e]) = tb;
+            *(U2 *)(sCT + tw_off[e]) = tc;
         }
     };
 
@@ -223,16 +257,16 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
     for (int ib = 0; ib < nblk; ++ib) {
         const int blk = REV ? (nblk - 1 - ib) : ib;
         const int t0 = seg_lo + blk * BK;
-        __syncthreads();                        // previous block's LDS readers are done
+        if (STATE_ONLY) __syncthreads();        // previous block's readers of sBT / sCT are done
         stage_block();
         __syncthreads();
         if (ib + 1 < nblk) load_block(REV ? blk - 1 : blk + 1);
 
-        // C^T fragments of this wave's slice: B operand of P C and of the state update
+        // C^T fragments of this wave's slice: operand of C^T P^T and of the state update
         U4 cf[KS_B];
 #pragma unroll
         for (int ks = 0; ks < KS_B; ++ks)
-            cf[ks] = *(const U4 *)(sCT + (32 * w + l32) * LDT + 16 * ks + 8 * g);
+            cf[ks] = *(const U4 *)(sCT + ct_row + 8 * ((2 * ks + g) ^ ct_phi));
 
         f32x16_t acc[2];
         if (!STATE_ONLY) {
@@ -254,31 +288,28 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
                     for (int v4 = 0; v4 < 4; ++v4) {
                         U2 p;
                         p[0] = pack2_bf16(s[4 * v4 + 0] * mk[ti][4 * v4 + 0],
-                                            s[4 * v4 + 1] * mk[ti][4 * v4 + 1]);
+                                          s[4 * v4 + 1] * mk[ti][4 * v4 + 1]);
                         p[1] = pack2_bf16(s[4 * v4 + 2] * mk[ti][4 * v4 + 2],
-                                            s[4 * v4 + 3] * mk[ti][4 * v4 + 3]);
+                                          s[4 * v4 + 3] * mk[ti][4 * v4 + 3]);
                         *(U2 *)(sP + (32 * qt + l32) * LDP + 32 * kt + 8 * v4 + 4 * g) = p;
                     }
                 }
             }
-            // ---- inter block: acc = rowscale * (A St), state operand from registers
+            // ---- inter block: acc^T = (St^T A^T) * scale(q); state operand from registers
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
                 f32x16_t x = {0};
 #pragma unroll
                 for (int ks = 0; ks < KS_D; ++ks) {
-                    const uint16_t *row = sA + (32 * mt + l32) * LDN + 16 * ks + 4 * g;
-                    U2 lo = *(const U2 *)(row);
-                    U2 hi = *(const U2 *)(row + 8);
-                    U4 fa = {lo[0], lo[1], hi[0], hi[1]};
-                    x = mfma32(fa, sf[ks], x);
+                    U4 fb = *(const U4 *)(sA + (32 * mt + l32) * LDN + 16 * ks + 8 * g);
+                    x = mfma32(sf[ks], fb, x);
                 }
 #pragma unroll
-                for (int v = 0; v < 16; ++v) x[v] *= rs16[v] * rs_tile[mt];
+                for (int v = 0; v < 16; ++v) x[v] *= rsq[mt];
                 acc[mt] = x;
             }
-            __syncthreads();                    // P is complete
-            // ---- intra block: acc += P C
+            __syncthreads();                    // P is complete; sB is free from here on
+            // ---- intra block: acc^T += C^T P^T
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll
@@ -286,11 +317,23 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
                     const int ktile = ks >> 1;
                     const bool live = REV ? (ktile >= mt) : (ktile <= mt);
                     if (live) {
-                        U4 fa = *(const U4 *)(sP + (32 * mt + l32) * LDP + 16 * ks + 8 * g);
-                        acc[mt] = mfma32(fa, cf[ks], acc[mt]);
+                        U4 fb = *(const U4 *)(sP + (32 * mt + l32) * LDP + 16 * ks + 8 * g);
+                        acc[mt] = mfma32(cf[ks], fb, acc[mt]);
                     }
                 }
             }
+            // ---- Out tile -> sO (bf16, sB's layout): lane holds 4 consecutive features per v4
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    U2 o;
+                    o[0] = pack2_bf16(acc[mt][4 * v4 + 0], acc[mt][4 * v4 + 1]);
+                    o[1] = pack2_bf16(acc[mt][4 * v4 + 2], acc[mt][4 * v4 + 3]);
+                    const int quad = 2 * (v4 & 1) + g;                 // quad of the 16-group
+                    const int pquad = (quad == 1) ? 2 : (quad == 2 ? 1 : quad);
+                    *(U2 *)(sO + (32 * mt + l32) * LDN + 32 * w + 16 * (v4 >> 1) + 4 * pquad) = o;
+                }
         }
 
         // ---- state update: St = lambda^BK St + (w Bm)^T C ---------------------------
@@ -301,7 +344,7 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
             for (int v = 0; v < 16; ++v) s[v] *= lamBK;
 #pragma unroll
             for (int ks = 0; ks < KS_B; ++ks) {
-                U4 fa = *(const U4 *)(sBT + (32 * mt + l32) * LDT + 16 * ks + 8 * g);
+                U4 fa = *(const U4 *)(sBT + bt_row[mt] + 8 * ((2 * ks + g) ^ bt_phi[mt]));
                 s = mfma32(fa, cf[ks], s);
             }
             st[mt] = s;
@@ -309,22 +352,14 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
 
         if (!STATE_ONLY) {
             refresh_state_operand();
-            __syncthreads();                    // all waves are done reading A and P
-            // ---- Out tile -> LDS (A's storage) as bf16, then full-row global stores
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int q = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
-                    const uint32_t pk = pack2_bf16(acc[mt][v], 0.0f);
-                    sA[q * LDN + 32 * w + l32] = (uint16_t)(pk & 0xffffu);
-                }
-            __syncthreads();
+            __syncthreads();                    // sO complete; every LDS tile of this block is dead
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int t = t0 + 4 * sa + i;
-                if (t < seg_hi)
-                    *(U4 *)(gO + (size_t)t * D + 8 * sc) = *(const U4 *)(sA + (4 * sa + i) * LDN + 8 * sc);
+                const uint16_t *po = sO + (4 * sa + i) * LDN + nat_off;
+                U2 lo = *(const U2 *)(po);
+                U2 hi = *(const U2 *)(po + 8);
+                if (t < seg_hi) *(U4 *)(gO + (size_t)t * D + 8 * sc) = U4{lo[0], lo[1], hi[0], hi[1]};
             }
         }
     }
