@@ -123,7 +123,7 @@ hipError_t allow_lds(K kernel, size_t bytes)
 }
 
 template <int D, bool REV, bool STATE_ONLY>
-hipError_t launch_bf16(const ScanArgs &a, const LaLambdas &lams, long scans, hipStream_t s)
+hipError_t launch_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
     using Cfg = Bf16Cfg<D>;
     auto kern = la_scan_bf16<D, REV, STATE_ONLY>;
@@ -131,13 +131,15 @@ hipError_t launch_bf16(const ScanArgs &a, const LaLambdas &lams, long scans, hip
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
     if (attr_err != hipSuccess) return attr_err;
-    dim3 grid((unsigned)(scans * a.S)), block(Cfg::NT);
+    // paired launch: two workgroups per item, items padded to a multiple of the 8 XCDs
+    const unsigned wgs = a.nroles == 2 ? 2u * (unsigned)((a.items + 7) / 8 * 8) : (unsigned)a.items;
+    dim3 grid(wgs), block(Cfg::NT);
     hipLaunchKernelGGL(kern, grid, block, Cfg::lds_bytes, s, a, lams);
     return hipGetLastError();
 }
 
 template <int D, int BK, bool REV, bool STATE_ONLY>
-hipError_t launch_f32(const ScanArgs &a, const LaLambdas &lams, long scans, hipStream_t s)
+hipError_t launch_f32(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
     using Cfg = F32Cfg<D, BK>;
     auto kern = la_scan_f32<D, BK, REV, STATE_ONLY>;
@@ -145,44 +147,97 @@ hipError_t launch_f32(const ScanArgs &a, const LaLambdas &lams, long scans, hipS
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
     if (attr_err != hipSuccess) return attr_err;
-    dim3 grid((unsigned)(scans * a.S)), block(Cfg::NT);
+    dim3 grid((unsigned)a.items), block(Cfg::NT);    // the fp32 path never pairs
     hipLaunchKernelGGL(kern, grid, block, Cfg::lds_bytes, s, a, lams);
     return hipGetLastError();
 }
 
 template <bool REV, bool STATE_ONLY>
-hipError_t launch_scan_kernel(const ScanArgs &a, const LaLambdas &lams, long scans, int d,
+hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
                               la_dtype dt, hipStream_t s)
 {
     if (dt == LA_BF16) {
-        if (d == 64) return launch_bf16<64, REV, STATE_ONLY>(a, lams, scans, s);
-        return launch_bf16<128, REV, STATE_ONLY>(a, lams, scans, s);
+        if (d == 64) return launch_bf16<64, REV, STATE_ONLY>(a, lams, s);
+        return launch_bf16<128, REV, STATE_ONLY>(a, lams, s);
     }
-    if (d == 64) return launch_f32<64, 64, REV, STATE_ONLY>(a, lams, scans, s);
-    return launch_f32<128, 32, REV, STATE_ONLY>(a, lams, scans, s);
+    if (d == 64) return launch_f32<64, 64, REV, STATE_ONLY>(a, lams, s);
+    return launch_f32<128, 32, REV, STATE_ONLY>(a, lams, s);
 }
 
-// One decayed causal scan Out = scan(A, Bm, C): [segment states -> segment scan ->] block scan.
+ScanArgs make_args(const void *A, const void *Bm, const void *C, void *Out, const Plan &p,
+                   int H, int n, float *states, int transpose_init)
+{
+    ScanArgs a;
+    a.A = A; a.Bm = Bm; a.C = C; a.Out = Out;
+    a.states = p.S > 1 ? states : nullptr;
+    a.n = n; a.H = H; a.L = p.L; a.S = p.S;
+    a.transpose_init = transpose_init;
+    return a;
+}
+
+// Segment-boundary states of scan(., Bm, C): local states per segment, then the
+// exclusive scan over segments, in place in `states`.
+template <bool REV>
+int run_segment_states(const ScanArgs &a, const LaLambdas &lams, long scans, int d, la_dtype dt,
+                       hipStream_t s)
+{
+    ScanLaunch l;
+    l.r[0] = a; l.r[1] = a; l.nroles = 1; l.items = (int)(scans * a.S);
+    if (launch_scan_kernel<REV, true>(l, lams, d, dt, s) != hipSuccess) return LA_ERR_LAUNCH;
+    SegScanArgs sa;
+    sa.states = a.states; sa.H = a.H; sa.S = a.S; sa.L = a.L; sa.DD = d * d;
+    dim3 grid((unsigned)((d * d + 255) / 256), (unsigned)scans), block(256);
+    hipLaunchKernelGGL(la_segment_scan<REV>, grid, block, 0, s, sa, lams);
+    return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+// One decayed causal scan Out = scan(A, Bm, C): [segment states ->] block scan.
 template <bool REV>
 int run_scan(const void *A, const void *Bm, const void *C, void *Out, const LaLambdas &lams,
              const Plan &p, int B, int H, int n, int d, la_dtype dt, float *states, hipStream_t s)
 {
     const long scans = (long)B * H;
-    ScanArgs a;
-    a.A = A; a.Bm = Bm; a.C = C; a.Out = Out;
-    a.states = p.S > 1 ? states : nullptr;
-    a.n = n; a.H = H; a.L = p.L; a.S = p.S;
+    const ScanArgs a = make_args(A, Bm, C, Out, p, H, n, states, 0);
     if (p.S > 1) {
-        if (launch_scan_kernel<REV, true>(a, lams, scans, d, dt, s) != hipSuccess) return LA_ERR_LAUNCH;
-        SegScanArgs sa;
-        sa.states = states; sa.H = H; sa.S = p.S; sa.L = p.L; sa.DD = d * d;
-        dim3 grid((unsigned)((d * d + 255) / 256), (unsigned)scans), block(256);
-        hipLaunchKernelGGL(la_segment_scan<REV>, grid, block, 0, s, sa, lams);
-        if (hipGetLastError() != hipSuccess) return LA_ERR_LAUNCH;
+        int rc = run_segment_states<REV>(a, lams, scans, d, dt, s);
+        if (rc != LA_OK) return rc;
     }
-    {
+    ScanLaunch l;
+    l.r[0] = a; l.r[1] = a; l.nroles = 1; l.items = (int)(scans * p.S);
+    ScopedTimer t(s);
+    return launch_scan_kernel<REV, false>(l, lams, d, dt, s) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+// The two reverse scans of Alg. 6's second loop,
+//     dK = scan_rev(V, dO, Q)   (state  sum w dO^T Q = dKV^T)
+//     dV = scan_rev(K, Q, dO)   (state  sum w Q^T dO = dKV),
+// share one set of segment states (dV reads dK's transposed) and, on the bf16
+// path, one paired launch in which the two workgroups of a segment sit on the
+// same XCD, so that dO and Q, which both read, come from HBM once.
+int run_reverse_pair(const void *Q, const void *K, const void *V, const void *dO, void *dK, void *dV,
+                     const LaLambdas &lams, const Plan &p, int B, int H, int n, int d, la_dtype dt,
+                     float *states, hipStream_t s)
+{
+    const long scans = (long)B * H;
+    const ScanArgs ak = make_args(V, dO, Q, dK, p, H, n, states, 0);
+    const ScanArgs av = make_args(K, Q, dO, dV, p, H, n, states, 1);
+    if (p.S > 1) {
+        int rc = run_segment_states<true>(ak, lams, scans, d, dt, s);
+        if (rc != LA_OK) return rc;
+    }
+    ScanLaunch l;
+    l.items = (int)(scans * p.S);
+    const bool pair = dt == LA_BF16 && std::getenv("LA_NO_PAIR") == nullptr;
+    if (pair) {
+        l.r[0] = ak; l.r[1] = av; l.nroles = 2;
         ScopedTimer t(s);
-        if (launch_scan_kernel<REV, false>(a, lams, scans, d, dt, s) != hipSuccess) return LA_ERR_LAUNCH;
+        return launch_scan_kernel<true, false>(l, lams, d, dt, s) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+    }
+    l.nroles = 1;
+    for (int i = 0; i < 2; ++i) {
+        l.r[0] = i == 0 ? ak : av; l.r[1] = l.r[0];
+        ScopedTimer t(s);
+        if (launch_scan_kernel<true, false>(l, lams, d, dt, s) != hipSuccess) return LA_ERR_LAUNCH;
     }
     return LA_OK;
 }
@@ -258,11 +313,8 @@ int la_bwd(const void *Q, const void *K, const void *V, const float *lambda, con
     // dQ = scan(dO, V, K): first loop of Alg. 6, state = KV^T
     rc = run_scan<false>(dO, V, K, dQ, lams, p, B, H, n, d, dt, ws, s);
     if (rc != LA_OK) return rc;
-    // dK = scan_rev(V, dO, Q): second loop of Alg. 6, state = dKV^T
-    rc = run_scan<true>(V, dO, Q, dK, lams, p, B, H, n, d, dt, ws, s);
-    if (rc != LA_OK) return rc;
-    // dV = scan_rev(K, Q, dO): second loop of Alg. 6, state = dKV
-    return run_scan<true>(K, Q, dO, dV, lams, p, B, H, n, d, dt, ws, s);
+    // dK = scan_rev(V, dO, Q) and dV = scan_rev(K, Q, dO): second loop of Alg. 6
+    return run_reverse_pair(Q, K, V, dO, dK, dV, lams, p, B, H, n, d, dt, ws, s);
 }
 
 const char *la_strerror(int status)

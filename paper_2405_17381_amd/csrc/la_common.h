@@ -49,6 +49,21 @@ struct ScanArgs {
     int H;               // heads (scan index % H selects lambda)
     int L;               // segment length in tokens (multiple of the tile length)
     int S;               // segments per scan
+    int transpose_init;  // the stored segment states are those of the scan with Bm and C
+                         // exchanged: read them transposed
+};
+
+// One launch of the block-scan kernel runs one scan, or two scans that read
+// mostly the same tensors (the dK and dV scans of Alg. 6's second loop).  In a
+// paired launch the two workgroups of one (scan, segment) item are placed on
+// the same XCD in consecutive dispatch slots, so that the tiles both of them
+// read are fetched from HBM once and served to the second reader from that
+// XCD's L2.  Workgroup ids go round-robin over the 8 XCDs:
+//   xcd = id % 8, slot = id / 8, role = slot % 2, item = (slot / 2) * 8 + xcd.
+struct ScanLaunch {
+    ScanArgs r[2];
+    int nroles;          // 1 or 2
+    int items;           // scans * S
 };
 
 // Segment scan over local segment states, in place:

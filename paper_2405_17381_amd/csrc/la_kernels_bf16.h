@@ -80,7 +80,7 @@ struct Bf16Cfg {
 };
 
 template <int D, bool REV, bool STATE_ONLY>
-__global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas lams)
+__global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLambdas lams)
 {
     using Cfg = Bf16Cfg<D>;
     constexpr int BK = Cfg::BK, NW = Cfg::NW;
@@ -103,8 +103,16 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
     const int w = tid >> 6, l = tid & 63, l32 = l & 31, g = l >> 5;
     const int sa = tid / CH, sc = tid % CH;    // staging: rows 4sa..4sa+3, chunk sc
 
-    const int seg = blockIdx.x % a.S;
-    const int scan = blockIdx.x / a.S;
+    int item = blockIdx.x, role = 0;
+    if (launch.nroles == 2) {
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        role = slot & 1;
+        item = (slot >> 1) * 8 + xcd;
+        if (item >= launch.items) return;
+    }
+    const ScanArgs &a = launch.r[role];
+    const int seg = item % a.S;
+    const int scan = item / a.S;
     if (STATE_ONLY) {
         if (!REV && seg == a.S - 1) return;    // never consumed
         if (REV && seg == 0) return;
@@ -180,7 +188,9 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             int i = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
-            st[mt][v] = has_init ? gSt[(size_t)i * D + 32 * w + l32] : 0.0f;
+            const size_t at = a.transpose_init ? (size_t)(32 * w + l32) * D + i
+                                               : (size_t)i * D + 32 * w + l32;
+            st[mt][v] = has_init ? gSt[at] : 0.0f;
         }
     U4 sf[KS_D];                               // bf16 copy of the state as an MFMA operand
     auto refresh_state_operand = [&]() {
@@ -192,9 +202,11 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
                 sf[ks][e] = pack2_bf16(st[mt][h8 + 2 * e], st[mt][h8 + 2 * e + 1]);
         }
     };
-    if (!STATE_ONLY) refresh_state_operand();
 
     // ---- global -> register prefetch of one block -------------------------------
+    // Rows past the segment end read the segment's last row instead (always in
+    // bounds); they are zeroed when the block is staged, so that nothing here
+    // consumes the loaded values and the loads stay in flight behind the compute.
     U4 ra[4], rb[4], rc[4];
     auto load_block = [&](int blk) {
         const int t0 = seg_lo + blk * BK;
@@ -202,21 +214,23 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
         for (int i = 0; i < 4; ++i) {
             const int t = t0 + 4 * sa + i;
             const size_t off = (size_t)min(t, seg_hi - 1) * D + 8 * sc;
-            // rows past the segment end read a valid row and are zeroed (zero padding)
-            const bool ok = t < seg_hi;
-            const U4 z = {0u, 0u, 0u, 0u};
             rb[i] = *(const U4 *)(gB + off);
             rc[i] = *(const U4 *)(gC + off);
-            rb[i] = ok ? rb[i] : z;
-            rc[i] = ok ? rc[i] : z;
-            if (!STATE_ONLY) {
-                ra[i] = *(const U4 *)(gA + off);
-                ra[i] = ok ? ra[i] : z;
-            }
+            if (!STATE_ONLY) ra[i] = *(const U4 *)(gA + off);
         }
     };
     // ---- registers -> LDS, transposing C and the weighted Bm ---------------------
-    auto stage_block = [&]() {
+    auto stage_block = [&](int t0) {
+        if (t0 + BK > seg_hi) {                 // partial block: zero padding (exact)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool ok = t0 + 4 * sa + i < seg_hi;
+                const U4 z = {0u, 0u, 0u, 0u};
+                rb[i] = ok ? rb[i] : z;
+                rc[i] = ok ? rc[i] : z;
+                if (!STATE_ONLY) ra[i] = ok ? ra[i] : z;
+            }
+        }
         if (!STATE_ONLY) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -258,15 +272,17 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
         const int blk = REV ? (nblk - 1 - ib) : ib;
         const int t0 = seg_lo + blk * BK;
         if (STATE_ONLY) __syncthreads();        // previous block's readers of sBT / sCT are done
-        stage_block();
+        stage_block(t0);
         __syncthreads();
         if (ib + 1 < nblk) load_block(REV ? blk - 1 : blk + 1);
 
-        // C^T fragments of this wave's slice: operand of C^T P^T and of the state update
-        U4 cf[KS_B];
+        U4 cf[KS_B];                            // C^T fragments of this wave's slice
+        auto load_cf = [&]() {
 #pragma unroll
-        for (int ks = 0; ks < KS_B; ++ks)
-            cf[ks] = *(const U4 *)(sCT + ct_row + 8 * ((2 * ks + g) ^ ct_phi));
+            for (int ks = 0; ks < KS_B; ++ks)
+                cf[ks] = *(const U4 *)(sCT + ct_row + 8 * ((2 * ks + g) ^ ct_phi));
+        };
+        if (STATE_ONLY) load_cf();
 
         f32x16_t acc[2];
         if (!STATE_ONLY) {
@@ -296,6 +312,7 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
                 }
             }
             // ---- inter block: acc^T = (St^T A^T) * scale(q); state operand from registers
+            refresh_state_operand();
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
                 f32x16_t x = {0};
@@ -309,6 +326,7 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
                 acc[mt] = x;
             }
             __syncthreads();                    // P is complete; sB is free from here on
+            load_cf();
             // ---- intra block: acc^T += C^T P^T
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
@@ -351,7 +369,6 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanArgs a, LaLambdas l
         }
 
         if (!STATE_ONLY) {
-            refresh_state_operand();
             __syncthreads();                    // sO complete; every LDS tile of this block is dead
 #pragma unroll
             for (int i = 0; i < 4; ++i) {

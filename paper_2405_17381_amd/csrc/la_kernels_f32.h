@@ -17,8 +17,9 @@ struct F32Cfg {
 };
 
 template <int D, int BK, bool REV, bool STATE_ONLY>
-__global__ __launch_bounds__(256) void la_scan_f32(ScanArgs a, LaLambdas lams)
+__global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas lams)
 {
+    const ScanArgs &a = launch.r[0];
     using Cfg = F32Cfg<D, BK>;
     constexpr int LD = Cfg::LD, LS = Cfg::LS, RI = Cfg::RI, CJ = Cfg::CJ;
     extern __shared__ float smem_f32[];
@@ -56,7 +57,7 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanArgs a, LaLambdas lams)
     const bool has_init = !STATE_ONLY && a.S > 1 && gSt != nullptr;
     for (int e = tid; e < D * D; e += 256) {
         int i = e / D, j = e % D;
-        sKV[i * LD + j] = has_init ? gSt[e] : 0.0f;
+        sKV[i * LD + j] = has_init ? (a.transpose_init ? gSt[j * D + i] : gSt[e]) : 0.0f;
     }
     __syncthreads();
     const float lamBK = sPw[BK];
