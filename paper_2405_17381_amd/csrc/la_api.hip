@@ -16,6 +16,11 @@ namespace {
 // MI355X: 256 compute units.  The planner is pure host arithmetic on purpose
 // (the workspace query must give the same answer with or without a GPU).
 constexpr int kComputeUnits = 256;
+// A sequence is cut into segments only when there are fewer (batch, head) scans
+// than compute units; it is then cut finely enough for two workgroups per unit.
+// Measured on the 64K-token sweep: one workgroup per unit without the segment-
+// state pre-pass beats two per unit with it, and 2048-token segments are best
+// among 512..8192.
 constexpr int kTargetWorkgroups = 2 * kComputeUnits;
 constexpr int kMinSegmentTokens = 512;
 
@@ -39,7 +44,7 @@ Plan make_plan(int B, int H, int n, int d, la_dtype dt)
     p.tile = tile_len(d, dt);
     const long scans = (long)B * H;
     int L = round_up(n, p.tile);
-    if (scans < kTargetWorkgroups) {
+    if (scans < kComputeUnits) {
         const long want = (kTargetWorkgroups + scans - 1) / scans;   // segments wanted per scan
         long l = (n + want - 1) / want;
         if (l < kMinSegmentTokens) l = kMinSegmentTokens;
@@ -186,7 +191,7 @@ int run_segment_states(const ScanArgs &a, const LaLambdas &lams, long scans, int
     if (launch_scan_kernel<REV, true>(l, lams, d, dt, s) != hipSuccess) return LA_ERR_LAUNCH;
     SegScanArgs sa;
     sa.states = a.states; sa.H = a.H; sa.S = a.S; sa.L = a.L; sa.DD = d * d;
-    dim3 grid((unsigned)((d * d + 255) / 256), (unsigned)scans), block(256);
+    dim3 grid((unsigned)((d * d / 4 + 255) / 256), (unsigned)scans), block(256);
     hipLaunchKernelGGL(la_segment_scan<REV>, grid, block, 0, s, sa, lams);
     return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }

@@ -195,22 +195,39 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
 // In-place exclusive scan of the segment states of each (batch, head):
 // forward  P_0 = 0, P_{s+1} = lambda^L P_s + S_s     (App. C, KV_t at segment granularity)
 // reverse  D_{S-1} = 0, D_{s-1} = lambda^L D_s + S_s (App. C, dKV_t likewise)
+// One thread carries four adjacent state entries through the segments; the
+// loads of a batch of eight segments are issued together (they do not depend
+// on the carry), only the stores follow the recurrence.
 template <bool REV>
 __global__ __launch_bounds__(256) void la_segment_scan(SegScanArgs a, LaLambdas lams)
 {
     const int scan = blockIdx.y;
-    const int e = blockIdx.x * 256 + threadIdx.x;
+    const int e = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (e >= a.DD) return;
     const float lam = lams.v[scan % a.H];
     const float lamL = (float)pow((double)lam, (double)a.L);
     float *W = a.states + (size_t)scan * a.S * a.DD + e;
-    float carry = 0.f;
-    for (int i = 0; i < a.S; ++i) {
-        const int s = REV ? (a.S - 1 - i) : i;
-        const bool last = (i == a.S - 1);
-        // the final segment's own local state was not produced and is not needed
-        float loc = last ? 0.f : W[(size_t)s * a.DD];
-        W[(size_t)s * a.DD] = carry;
-        carry = fmaf(lamL, carry, loc);
+    float4 carry = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i0 = 0; i0 < a.S; i0 += 8) {
+        float4 loc[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u;
+            const int s = REV ? (a.S - 1 - i) : i;
+            // the final segment's own local state was not produced and is not needed
+            loc[u] = (i < a.S - 1) ? *(const float4 *)(W + (size_t)s * a.DD) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u;
+            if (i < a.S) {
+                const int s = REV ? (a.S - 1 - i) : i;
+                *(float4 *)(W + (size_t)s * a.DD) = carry;
+                carry.x = fmaf(lamL, carry.x, loc[u].x);
+                carry.y = fmaf(lamL, carry.y, loc[u].y);
+                carry.z = fmaf(lamL, carry.z, loc[u].z);
+                carry.w = fmaf(lamL, carry.w, loc[u].w);
+            }
+        }
     }
 }
