@@ -61,6 +61,10 @@ __device__ __forceinline__ f32x16_t mfma32(const U4 &a, const U4 &b, f32x16_t c)
                                                    __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
 }
 
+// Scheduling fence between a batch of LDS operand loads and the MFMAs that use
+// them: LDS instructions and MFMAs may not cross it, everything else may.
+#define LA_BATCH_FENCE() __builtin_amdgcn_sched_barrier(0x476)
+
 // Transposed-tile addressing, in bf16 elements: feature f (row), block row r.
 //   physical row   = f with bits 0 and 3 swapped (so that the 16 features 8*sc+e
 //                    written by one store instruction fall on both bank halves)
@@ -141,21 +145,14 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
     const float lamBK = pw(BK);
     // row-major tiles: this thread's two 8-byte pieces of chunk sc
     const int nat_off = 16 * (sc >> 1) + 4 * (sc & 1);
-    // transposed tiles: element offsets of this thread's 8 stores (feature 8sc+e)
-    int tw_off[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int f = 8 * sc + e;
-        tw_off[e] = tt_row(f) * BK + 8 * ((sa >> 1) ^ tt_phi(f)) + 4 * (sa & 1);
-    }
-    // transposed tiles: operand rows read by this lane
-    const int ct_row = tt_row(32 * w + l32) * BK, ct_phi = tt_phi(32 * w + l32);
-    int bt_row[MT_D], bt_phi[MT_D];
-#pragma unroll
-    for (int mt = 0; mt < MT_D; ++mt) {
-        bt_row[mt] = tt_row(32 * mt + l32) * BK;
-        bt_phi[mt] = tt_phi(32 * mt + l32);
-    }
+    // transposed tiles, stores: feature f = 8sc + e lives in physical row
+    // tt_row(f) = tw_row + ((e&1)<<3 | (e&6)) and chunk (sa>>1) ^ tt_phi(f) = tw_u ^ e
+    const int tw_row = (((sc >> 1) << 4) | (sc & 1)) * BK + 4 * (sa & 1);
+    int tw_u = 8 * ((sa >> 1) ^ ((sc >> 1) & 7));
+    // transposed tiles, operand loads: feature f = 32m + l32 lives in physical row
+    // 32m + tt_row(l32), and chunk (2ks+g) ^ tt_phi(f) = tr_pg ^ 2(ks ^ m)
+    const int tr_row = tt_row(l32) * BK;
+    int tr_pg = 8 * (((l32 & 7) ^ (l32 >> 4)) ^ g);
 
     float rsq[2];                              // inter-block scale of column q = 32mt + l32
     float mk[NTILE][16];                       // decay mask of this wave's score tiles
@@ -183,25 +180,35 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
     // ---- running state: St[i][j], j in this wave's slice ----------------------
     f32x16_t st[MT_D];
     const bool has_init = !STATE_ONLY && a.S > 1 && gSt != nullptr;
-#pragma unroll
-    for (int mt = 0; mt < MT_D; ++mt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            int i = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
-            const size_t at = a.transpose_init ? (size_t)(32 * w + l32) * D + i
-                                               : (size_t)i * D + 32 * w + l32;
-            st[mt][v] = has_init ? gSt[at] : 0.0f;
+    if (has_init && a.transpose_init) {
+        // The stored state is that of the scan with Bm and C exchanged: copy it to LDS
+        // with coalesced 16-byte loads (the tiles' storage is still unused) and read it
+        // back transposed, so that this workgroup starts as quickly as its partner of
+        // a paired launch and the two stay in step.
+        float *sT = reinterpret_cast<float *>(smem_bf16);          // [D][D+1]
+        for (int e = tid * 4; e < D * D; e += 4 * Cfg::NT) {
+            const float4 x = *(const float4 *)(gSt + e);
+            float *q = sT + (e / D) * (D + 1) + (e % D);
+            q[0] = x.x; q[1] = x.y; q[2] = x.z; q[3] = x.w;
         }
-    U4 sf[KS_D];                               // bf16 copy of the state as an MFMA operand
-    auto refresh_state_operand = [&]() {
+        __syncthreads();
 #pragma unroll
-        for (int ks = 0; ks < KS_D; ++ks) {
-            const int mt = ks >> 1, h8 = 8 * (ks & 1);
+        for (int mt = 0; mt < MT_D; ++mt)
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                sf[ks][e] = pack2_bf16(st[mt][h8 + 2 * e], st[mt][h8 + 2 * e + 1]);
-        }
-    };
+            for (int v = 0; v < 16; ++v) {
+                int i = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
+                st[mt][v] = sT[(32 * w + l32) * (D + 1) + i];
+            }
+        __syncthreads();
+    } else {
+#pragma unroll
+        for (int mt = 0; mt < MT_D; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int i = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
+                st[mt][v] = has_init ? gSt[(size_t)i * D + 32 * w + l32] : 0.0f;
+            }
+    }
 
     // ---- global -> register prefetch of one block -------------------------------
     // Rows past the segment end read the segment's last row instead (always in
@@ -261,8 +268,9 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
             }
             tb[0] = pack2_bf16(b0 * wst[0], b1 * wst[1]);
             tb[1] = pack2_bf16(b2 * wst[2], b3 * wst[3]);
-            *(U2 *)(sBT + tw_off[e]) = tb;
-            *(U2 *)(sCT + tw_off[e]) = tc;
+            const int off = tw_row + (((e & 1) << 3) | (e & 6)) * BK + (tw_u ^ (8 * e));
+            *(U2 *)(sBT + off) = tb;
+            *(U2 *)(sCT + off) = tc;
         }
     };
 
@@ -271,6 +279,9 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
     for (int ib = 0; ib < nblk; ++ib) {
         const int blk = REV ? (nblk - 1 - ib) : ib;
         const int t0 = seg_lo + blk * BK;
+        // the swizzle terms are re-derived per block (one XOR each) instead of living
+        // in a register per address for the whole loop
+        asm volatile("" : "+v"(tw_u), "+v"(tr_pg));
         if (STATE_ONLY) __syncthreads();        // previous block's readers of sBT / sCT are done
         stage_block(t0);
         __syncthreads();
@@ -280,10 +291,14 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         auto load_cf = [&]() {
 #pragma unroll
             for (int ks = 0; ks < KS_B; ++ks)
-                cf[ks] = *(const U4 *)(sCT + ct_row + 8 * ((2 * ks + g) ^ ct_phi));
+                cf[ks] = *(const U4 *)(sCT + 32 * w * BK + tr_row + (tr_pg ^ (16 * (ks ^ (w & 3)))));
         };
         if (STATE_ONLY) load_cf();
 
+        // Operand fragments are read from LDS in batches of eight 16-byte loads that
+        // are all issued before the MFMAs that consume them (a scheduling barrier keeps
+        // the compiler from sinking each load next to its use): the LDS latency is paid
+        // once per batch instead of once per MFMA.
         f32x16_t acc[2];
         if (!STATE_ONLY) {
             // ---- scores: S^T tile (kt, qt) = Bm[kt] A[qt]^T, masked, to LDS as P[q][key]
@@ -293,12 +308,20 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
                 if (tile < 3) {
                     const int kt = REV ? (tile >= 1) : (tile == 2);
                     const int qt = REV ? (tile == 2) : (tile >= 1);
+                    const uint16_t *pa = sB + (32 * kt + l32) * LDN + 8 * g;
+                    const uint16_t *pb = sA + (32 * qt + l32) * LDN + 8 * g;
                     f32x16_t s = {0};
 #pragma unroll
-                    for (int ks = 0; ks < KS_D; ++ks) {
-                        U4 fa = *(const U4 *)(sB + (32 * kt + l32) * LDN + 16 * ks + 8 * g);
-                        U4 fb = *(const U4 *)(sA + (32 * qt + l32) * LDN + 16 * ks + 8 * g);
-                        s = mfma32(fa, fb, s);
+                    for (int h = 0; h < KS_D / 4; ++h) {
+                        U4 fa[4], fb[4];
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            fa[k] = *(const U4 *)(pa + 16 * (4 * h + k));
+                            fb[k] = *(const U4 *)(pb + 16 * (4 * h + k));
+                        }
+                        LA_BATCH_FENCE();
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) s = mfma32(fa[k], fb[k], s);
                     }
 #pragma unroll
                     for (int v4 = 0; v4 < 4; ++v4) {
@@ -311,34 +334,59 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
                     }
                 }
             }
-            // ---- inter block: acc^T = (St^T A^T) * scale(q); state operand from registers
-            refresh_state_operand();
+            // ---- inter block: acc^T = (St^T A^T) * scale(q).  The state operand is made
+            // from the accumulator registers k-step by k-step and used for both q tiles.
+            {
+                f32x16_t x0 = {0}, x1 = {0};
+                const uint16_t *p0 = sA + l32 * LDN + 8 * g;
+                const uint16_t *p1 = sA + (32 + l32) * LDN + 8 * g;
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                f32x16_t x = {0};
+                for (int h = 0; h < KS_D / 2; ++h) {
+                    U4 f0[2], f1[2];
 #pragma unroll
-                for (int ks = 0; ks < KS_D; ++ks) {
-                    U4 fb = *(const U4 *)(sA + (32 * mt + l32) * LDN + 16 * ks + 8 * g);
-                    x = mfma32(sf[ks], fb, x);
-                }
+                    for (int k = 0; k < 2; ++k) {
+                        f0[k] = *(const U4 *)(p0 + 16 * (2 * h + k));
+                        f1[k] = *(const U4 *)(p1 + 16 * (2 * h + k));
+                    }
+                    LA_BATCH_FENCE();
 #pragma unroll
-                for (int v = 0; v < 16; ++v) x[v] *= rsq[mt];
-                acc[mt] = x;
-            }
-            __syncthreads();                    // P is complete; sB is free from here on
-            load_cf();
-            // ---- intra block: acc^T += C^T P^T
+                    for (int k = 0; k < 2; ++k) {
+                        const int ks = 2 * h + k, mt = ks >> 1, h8 = 8 * (ks & 1);
+                        U4 so;
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-                for (int ks = 0; ks < KS_B; ++ks) {
-                    const int ktile = ks >> 1;
-                    const bool live = REV ? (ktile >= mt) : (ktile <= mt);
-                    if (live) {
-                        U4 fb = *(const U4 *)(sP + (32 * mt + l32) * LDP + 16 * ks + 8 * g);
-                        acc[mt] = mfma32(cf[ks], fb, acc[mt]);
+                        for (int e = 0; e < 4; ++e)
+                            so[e] = pack2_bf16(st[mt][h8 + 2 * e], st[mt][h8 + 2 * e + 1]);
+                        x0 = mfma32(so, f0[k], x0);
+                        x1 = mfma32(so, f1[k], x1);
                     }
                 }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) { x0[v] *= rsq[0]; x1[v] *= rsq[1]; }
+                acc[0] = x0;
+                acc[1] = x1;
+            }
+            __syncthreads();                    // P is complete; sB is free from here on
+            // ---- intra block: acc^T += C^T P^T
+            {
+                U4 fp[2][KS_B];
+                load_cf();
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int ks = 0; ks < KS_B; ++ks) {
+                        const int ktile = ks >> 1;
+                        const bool live = REV ? (ktile >= mt) : (ktile <= mt);
+                        if (live) fp[mt][ks] = *(const U4 *)(sP + (32 * mt + l32) * LDP + 16 * ks + 8 * g);
+                    }
+                LA_BATCH_FENCE();
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int ks = 0; ks < KS_B; ++ks) {
+                        const int ktile = ks >> 1;
+                        const bool live = REV ? (ktile >= mt) : (ktile <= mt);
+                        if (live) acc[mt] = mfma32(cf[ks], fp[mt][ks], acc[mt]);
+                    }
             }
             // ---- Out tile -> sO (bf16, sB's layout): lane holds 4 consecutive features per v4
 #pragma unroll
@@ -357,14 +405,16 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         // ---- state update: St = lambda^BK St + (w Bm)^T C ---------------------------
 #pragma unroll
         for (int mt = 0; mt < MT_D; ++mt) {
+            U4 fa[KS_B];
+#pragma unroll
+            for (int ks = 0; ks < KS_B; ++ks)
+                fa[ks] = *(const U4 *)(sBT + 32 * mt * BK + tr_row + (tr_pg ^ (16 * (ks ^ mt))));
+            LA_BATCH_FENCE();
             f32x16_t s = st[mt];
 #pragma unroll
             for (int v = 0; v < 16; ++v) s[v] *= lamBK;
 #pragma unroll
-            for (int ks = 0; ks < KS_B; ++ks) {
-                U4 fa = *(const U4 *)(sBT + bt_row[mt] + 8 * ((2 * ks + g) ^ bt_phi[mt]));
-                s = mfma32(fa, cf[ks], s);
-            }
+            for (int ks = 0; ks < KS_B; ++ks) s = mfma32(fa[ks], cf[ks], s);
             st[mt] = s;
         }
 
