@@ -177,6 +177,9 @@ ScanArgs make_args(const void *A, const void *Bm, const void *C, void *Out, cons
     a.states = p.S > 1 ? states : nullptr;
     a.n = n; a.H = H; a.L = p.L; a.S = p.S;
     a.transpose_init = transpose_init;
+    // Pre-pass cut-off: 2^-48 of the nearest row's weight, far below the 2^-24
+    // resolution of the fp32 state it is added to (LA_NO_DECAY_SKIP reads everything).
+    a.skip_bits = std::getenv("LA_NO_DECAY_SKIP") ? 0.0f : 48.0f;
     return a;
 }
 

@@ -49,6 +49,8 @@ struct ScanArgs {
     int H;               // heads (scan index % H selects lambda)
     int L;               // segment length in tokens (multiple of the tile length)
     int S;               // segments per scan
+    float skip_bits;     // segment-state pre-pass only: rows whose decay weight is below
+                         // 2^-skip_bits are not read (0 = read everything)
     int transpose_init;  // the stored segment states are those of the scan with Bm and C
                          // exchanged: read them transposed
 };

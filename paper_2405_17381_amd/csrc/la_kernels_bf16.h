@@ -274,9 +274,19 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         }
     };
 
-    load_block(REV ? nblk - 1 : 0);
+    // Pre-pass only: the local state of a segment weights row r by lambda^(distance to
+    // the segment's far end).  Blocks whose largest weight is below 2^-skip_bits add
+    // less than fp32 rounding to a state whose nearest rows have weight 1, so they are
+    // not read at all: with decay, far context is numerically irrelevant.
+    int ib0 = 0;
+    if (STATE_ONLY && a.skip_bits > 0.f && lg < 0.f) {
+        const float reach = a.skip_bits / -lg;          // rows that still matter
+        if (reach < (float)(nblk * BK)) ib0 = max(0, nblk - ((int)(reach / BK) + 2));
+    }
 
-    for (int ib = 0; ib < nblk; ++ib) {
+    load_block(REV ? nblk - 1 - ib0 : ib0);
+
+    for (int ib = ib0; ib < nblk; ++ib) {
         const int blk = REV ? (nblk - 1 - ib) : ib;
         const int t0 = seg_lo + blk * BK;
         // the swizzle terms are re-derived per block (one XOR each) instead of living

@@ -62,7 +62,12 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
     __syncthreads();
     const float lamBK = sPw[BK];
 
-    for (int ib = 0; ib < nblk; ++ib) {
+    int ib0 = 0;     // pre-pass: skip blocks whose decay weights are below 2^-skip_bits
+    if (STATE_ONLY && a.skip_bits > 0.f && lam < 1.0f) {
+        const float reach = a.skip_bits / -log2f(lam);
+        if (reach < (float)(nblk * BK)) ib0 = max(0, nblk - ((int)(reach / BK) + 2));
+    }
+    for (int ib = ib0; ib < nblk; ++ib) {
         const int blk = REV ? (nblk - 1 - ib) : ib;
         const int t0 = seg_lo + blk * BK;
         // ---- load tiles (rows past the segment end are zero) ----

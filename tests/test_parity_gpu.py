@@ -133,6 +133,28 @@ def test_result_independent_of_segmentation_bf16():
             assert oracle.rel_max_err(b, a) <= 1e-2, lseg
 
 
+def test_decay_cutoff_of_the_prepass_is_invisible():
+    """The segment-state pre-pass does not read rows whose decay weight is below
+    2^-48; against reading everything the outputs may differ by fp32 rounding of
+    the state at most."""
+    lam = [0.5, 0.9, 0.95, 0.98, 0.9999, 1.0]
+    w = synth.custom(1, len(lam), 8192, 128, lam, seed=99, dtype="bf16")
+    xs = synth.draw(w)
+    cut = _run_gpu(w, xs, lseg=2048)
+    os.environ["LA_NO_DECAY_SKIP"] = "1"
+    try:
+        full = _run_gpu(w, xs, lseg=2048)
+    finally:
+        os.environ.pop("LA_NO_DECAY_SKIP", None)
+    for a, b in zip(cut, full):
+        assert oracle.rel_max_err(a, b) <= 1e-5
+    q, k, v, g = _ref_inputs(xs, "bf16")
+    ref = (oracle.c_recurrence_fwd(q, k, v, lam),) + oracle.c_recurrence_bwd(q, k, v, lam, g)
+    _compare(w, cut, ref, TOL["bf16"], "decay cut-off, n=8192, L=2048")
+    wf = synth.custom(1, len(lam), 1024, 64, lam, seed=98, dtype="f32")
+    _full_case(wf, lseg=256)
+
+
 def test_bitwise_reproducible():
     w = synth.custom(2, 4, 1500, 128, [1.0, 0.99, 0.9, 0.5], seed=5, dtype="bf16")
     xs = synth.draw(w)
