@@ -17,7 +17,7 @@ import subprocess
 
 import numpy as np
 
-from .la_oracle import (decay_matrix, left_product_bwd, left_product_fwd,
+from .la_oracle import (decay_matrix, decode_step, left_product_bwd, left_product_fwd,
                         recurrence_bwd, recurrence_fwd, rel_max_err)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -89,18 +89,38 @@ def left_product_bwd(Q, K, V, lam, dO):
 # --------------------------------------------------------------------------
 # form (ii): token-by-token recurrence
 # --------------------------------------------------------------------------
-def recurrence_fwd(Q, K, V, lam):
+def recurrence_fwd(Q, K, V, lam, kv0=None, return_state=False):
+    """Token recurrence.  With `kv0` ([B, H, d, d]) the recurrence starts from
+    that state instead of zero (the state left by earlier tokens: Sec. 3.1 notes
+    that inference only ever needs this d x d state); with `return_state` the
+    state after the last token, kv_n, is returned as well."""
     Q, K, V = _as64(Q), _as64(K), _as64(V)
     B, H, n, d = Q.shape
     O = np.empty_like(Q)
+    KVn = np.empty((B, H, d, d), dtype=np.float64)
     for b in range(B):
         for h in range(H):
             l = float(lam[h])
-            kv = np.zeros((d, d), dtype=np.float64)
+            kv = np.zeros((d, d), dtype=np.float64) if kv0 is None else _as64(kv0)[b, h].copy()
             for t in range(n):
                 kv = l * kv + np.outer(K[b, h, t], V[b, h, t])
                 O[b, h, t] = Q[b, h, t] @ kv
-    return O
+            KVn[b, h] = kv
+    return (O, KVn) if return_state else O
+
+
+def decode_step(q, k, v, lam, kv):
+    """One token of the recurrence (App. A, recurrence form): kv' = lam kv + k v^T,
+    o = q^T kv'.  q, k, v: [B, H, d]; kv: [B, H, d, d].  Returns (o, kv')."""
+    q, k, v, kv = _as64(q), _as64(k), _as64(v), _as64(kv)
+    B, H, d = q.shape
+    o = np.empty_like(q)
+    kv_new = np.empty_like(kv)
+    for b in range(B):
+        for h in range(H):
+            kv_new[b, h] = float(lam[h]) * kv[b, h] + np.outer(k[b, h], v[b, h])
+            o[b, h] = q[b, h] @ kv_new[b, h]
+    return o, kv_new
 
 
 def recurrence_bwd(Q, K, V, lam, dO):

@@ -256,3 +256,35 @@ def test_planted_exclusive_diagonal_fails_example_a():
         O[t] = Q[t] @ kv                                    # wrong: state before update
         kv = g["lambda"] * kv + np.outer(K[t], V[t])
     assert np.max(np.abs(O - g["O"][0, 0])) > 0.5
+
+
+# ---- 10. carried state: prefill in pieces and token-by-token decode -----------------
+@pytest.mark.parametrize("lam", [1.0, 0.9, 0.2])
+def test_state_carry_splits_the_sequence(lam):
+    """Running the first m tokens, keeping kv_m, and continuing from it gives
+    the same outputs as one run (the block form of App. C with blocks m, n-m),
+    and the returned state is sum_s lam^(n-s) k_s v_s^T (App. C, KV_t)."""
+    n, d, m = 13, 3, 5
+    Q, K, V, _ = _rand(1, 1, n, d, seed=51)
+    O_all = oracle.left_product_fwd(Q, K, V, [lam])
+    O1, kv_m = oracle.recurrence_fwd(Q[:, :, :m], K[:, :, :m], V[:, :, :m], [lam], return_state=True)
+    O2, kv_n = oracle.recurrence_fwd(Q[:, :, m:], K[:, :, m:], V[:, :, m:], [lam], kv0=kv_m,
+                                     return_state=True)
+    np.testing.assert_allclose(np.concatenate([O1, O2], axis=2), O_all, rtol=1e-11, atol=1e-12)
+    w = lam ** (n - 1 - np.arange(n, dtype=np.float64))
+    expect = (K[0, 0] * w[:, None]).T @ V[0, 0]
+    np.testing.assert_allclose(kv_n[0, 0], expect, rtol=1e-11, atol=1e-12)
+
+
+def test_decode_steps_reproduce_the_sequence():
+    n, d, lam = 9, 4, [0.8, 1.0]
+    Q, K, V, _ = _rand(2, 2, n, d, seed=52)
+    O_all = oracle.left_product_fwd(Q, K, V, lam)
+    kv = np.zeros((2, 2, d, d))
+    for t in range(n):
+        o, kv = oracle.decode_step(Q[:, :, t], K[:, :, t], V[:, :, t], lam, kv)
+        np.testing.assert_allclose(o, O_all[:, :, t], rtol=1e-11, atol=1e-12)
+    # worked example A: the state after the three tokens is 7.25
+    g = load_golden("worked_example_a.txt")
+    _, kv3 = oracle.recurrence_fwd(g["Q"], g["K"], g["V"], [g["lambda"]], return_state=True)
+    assert abs(kv3[0, 0, 0, 0] - 7.25) < 1e-14
