@@ -186,6 +186,31 @@ def main():
                 "launches": launches, "avg_launch_ms": round(scan_ms / max(launches, 1), 5),
                 "algorithmic_bytes_per_launch": round(per_launch)}
 
+    # ---- decode step (next row after the training path): B=8, H=32, d=128, bf16 ----------
+    # One token per (batch, head) streams the fp32 d x d state in and out: 2 * 4 d^2 bytes.
+    dB, dH = 8, 32
+    dlam = synth.workload("c4").lambdas
+    kv = torch.zeros(dB, dH, D, D, device=dev, dtype=torch.float32)
+    qkv = [(torch.randn(dB, dH, D, device=dev) * scale).to(torch.bfloat16) for _ in range(3)]
+    o1 = torch.empty_like(qkv[0])
+    for _ in range(10):
+        binding.la_decode_step(qkv[0], qkv[1], qkv[2], dlam, kv, o=o1)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    dsteps = 200
+    for _ in range(dsteps):
+        binding.la_decode_step(qkv[0], qkv[1], qkv[2], dlam, kv, o=o1)
+    e1.record()
+    e1.synchronize()
+    dec_ms = e0.elapsed_time(e1) / dsteps
+    dec_bytes = 2 * 4 * D * D * dB * dH
+    decode = {"workload": "la_decode_step, B=8, H=32, d=128, bf16 tokens, fp32 state in place",
+              "ms_per_step": round(dec_ms, 5), "tokens_per_s": round(dB / (dec_ms * 1e-3), 1),
+              "algorithmic_bytes_per_step": dec_bytes,
+              "achieved_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
+              "note": "includes launch overhead of one small kernel per step; 32 MiB of state per step"}
+
     total_tflops = value * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12
     out = {
         "metric": "fwd+bwd tokens/s (causal linear attention with decay, bf16, d=128, seq-len sweep "
@@ -202,6 +227,7 @@ def main():
         "pct_mfma_bf16_peak": round(100.0 * total_tflops / MFMA_BF16_PEAK_TFLOPS, 2),
         "sweep": sweep,
         "roofline": roofline,
+        "decode": decode,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()

@@ -101,6 +101,35 @@ int la_bwd(const void *Q, const void *K, const void *V,
            int B, int H, int n, int d, la_dtype dt,
            void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Forward pass with a carried state (the next step after la_fwd / la_bwd: the
+ * paper's inference use, Sec. 3.1, where only the d x d state K^T V is kept
+ * between calls; the recurrence is App. A's with kv_0 = kv_in):
+ *     kv_{-1} = kv_in ;  kv_t = lambda kv_{t-1} + k_t v_t^T ;  o_t^T = q_t^T kv_t ;
+ *     kv_out = kv_{n-1}.
+ * kv_in, kv_out: DEVICE pointers to [B, H, d, d] fp32 (rows = key feature,
+ * columns = value feature), 16-byte aligned; either may be NULL (zero state in,
+ * no state out); they may be the same buffer.  Everything else as la_fwd; with
+ * both NULL this is la_fwd.  Long prompts can be fed in pieces of any length.
+ */
+int la_fwd_state(const void *Q, const void *K, const void *V,
+                 const float *lambda /* host, [H] */,
+                 void *O, const float *kv_in, float *kv_out,
+                 int B, int H, int n, int d, la_dtype dt,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * One decode token (App. A, recurrence form), for every (batch, head):
+ *     kv <- lambda kv + k v^T ;  o = q^T kv.
+ * q, k, v: inputs [B, H, d] of type dt; o: output [B, H, d] of type dt;
+ * kv: [B, H, d, d] fp32, updated IN PLACE; all DEVICE pointers, kv 16-byte
+ * aligned.  fp32 arithmetic whatever dt is.  Needs no workspace.
+ */
+int la_decode_step(const void *q, const void *k, const void *v,
+                   const float *lambda /* host, [H] */,
+                   float *kv, void *o,
+                   int B, int H, int d, la_dtype dt, void *hip_stream);
+
 /* Static, human-readable text for an la_status value. */
 const char *la_strerror(int status);
 

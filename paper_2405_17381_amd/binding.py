@@ -15,7 +15,7 @@ import torch
 LA_F32, LA_BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libla.so")
-EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_strerror", "la_plan",
+EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_fwd_state", "la_decode_step", "la_strerror", "la_plan",
            "la_profile_enable", "la_profile_collect")
 _lib = None
 
@@ -42,6 +42,10 @@ def load_library():
     lib.la_fwd.restype = ci
     lib.la_bwd.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.la_bwd.restype = ci
+    lib.la_fwd_state.argtypes = [vp, vp, vp, fp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.la_fwd_state.restype = ci
+    lib.la_decode_step.argtypes = [vp, vp, vp, fp, vp, vp, ci, ci, ci, ci, vp]
+    lib.la_decode_step.restype = ci
     lib.la_strerror.argtypes = [ci]
     lib.la_strerror.restype = ctypes.c_char_p
     ip = ctypes.POINTER(ci)
@@ -126,6 +130,57 @@ def la_fwd(Q, K, V, lam, O=None, workspace: Optional[torch.Tensor] = None):
     if rc != 0:
         raise LaError(rc, "la_fwd")
     return O
+
+
+def _check_state(kv, B, H, d, device):
+    if kv is None:
+        return 0
+    if (not kv.is_cuda) or kv.dtype != torch.float32 or tuple(kv.shape) != (B, H, d, d) \
+            or not kv.is_contiguous() or kv.device != device:
+        raise ValueError("la: state must be a contiguous float32 [B, H, d, d] tensor on the same GPU")
+    return kv.data_ptr()
+
+
+def la_fwd_state(Q, K, V, lam, kv_in=None, kv_out=None, O=None, workspace: Optional[torch.Tensor] = None):
+    """O = forward pass starting from state kv_in; the state after the last token is
+    written to kv_out ([B, H, d, d] float32; either may be None; may be the same tensor)."""
+    _check([Q, K, V])
+    B, H, n, d = Q.shape
+    if O is None:
+        O = torch.empty_like(Q)
+    else:
+        _check([Q, O])
+    dt = _dt(Q)
+    p_in, p_out = _check_state(kv_in, B, H, d, Q.device), _check_state(kv_out, B, H, d, Q.device)
+    ws, ws_ptr, ws_bytes = _workspace(B, H, n, d, dt, False, Q.device, workspace)
+    with torch.cuda.device(Q.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_fwd_state(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _lam(lam, H),
+                                         O.data_ptr(), p_in, p_out, B, H, n, d, dt, ws_ptr, ws_bytes, stream)
+    if rc != 0:
+        raise LaError(rc, "la_fwd_state")
+    return O
+
+
+def la_decode_step(q, k, v, lam, kv, o=None):
+    """One token: kv <- lambda kv + k v^T (in place), o = q^T kv.  q, k, v: [B, H, d]."""
+    for t in (q, k, v):
+        if t.dim() != 3 or not t.is_cuda or not t.is_contiguous() or t.shape != q.shape or t.dtype != q.dtype:
+            raise ValueError("la: q, k, v must be contiguous [B, H, d] GPU tensors of one dtype")
+    B, H, d = q.shape
+    o = torch.empty_like(q) if o is None else o
+    if o.shape != q.shape or o.dtype != q.dtype or not o.is_cuda or not o.is_contiguous():
+        raise ValueError("la: o must match q")
+    p_kv = _check_state(kv, B, H, d, q.device)
+    if p_kv == 0:
+        raise ValueError("la: kv is required")
+    with torch.cuda.device(q.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_decode_step(q.data_ptr(), k.data_ptr(), v.data_ptr(), _lam(lam, H),
+                                           p_kv, o.data_ptr(), B, H, d, _dt(q), stream)
+    if rc != 0:
+        raise LaError(rc, "la_decode_step")
+    return o
 
 
 def la_bwd(Q, K, V, lam, dO, dQ=None, dK=None, dV=None, workspace: Optional[torch.Tensor] = None):

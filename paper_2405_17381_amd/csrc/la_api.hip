@@ -180,6 +180,8 @@ ScanArgs make_args(const void *A, const void *Bm, const void *C, void *Out, cons
     // Pre-pass cut-off: 2^-48 of the nearest row's weight, far below the 2^-24
     // resolution of the fp32 state it is added to (LA_NO_DECAY_SKIP reads everything).
     a.skip_bits = std::getenv("LA_NO_DECAY_SKIP") ? 0.0f : 48.0f;
+    a.st_in = nullptr;
+    a.st_out = nullptr;
     return a;
 }
 
@@ -193,7 +195,8 @@ int run_segment_states(const ScanArgs &a, const LaLambdas &lams, long scans, int
     l.r[0] = a; l.r[1] = a; l.nroles = 1; l.items = (int)(scans * a.S);
     if (launch_scan_kernel<REV, true>(l, lams, d, dt, s) != hipSuccess) return LA_ERR_LAUNCH;
     SegScanArgs sa;
-    sa.states = a.states; sa.H = a.H; sa.S = a.S; sa.L = a.L; sa.DD = d * d;
+    sa.states = a.states; sa.init = REV ? nullptr : a.st_in;
+    sa.H = a.H; sa.S = a.S; sa.L = a.L; sa.DD = d * d;
     dim3 grid((unsigned)((d * d / 4 + 255) / 256), (unsigned)scans), block(256);
     hipLaunchKernelGGL(la_segment_scan<REV>, grid, block, 0, s, sa, lams);
     return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
@@ -202,10 +205,13 @@ int run_segment_states(const ScanArgs &a, const LaLambdas &lams, long scans, int
 // One decayed causal scan Out = scan(A, Bm, C): [segment states ->] block scan.
 template <bool REV>
 int run_scan(const void *A, const void *Bm, const void *C, void *Out, const LaLambdas &lams,
-             const Plan &p, int B, int H, int n, int d, la_dtype dt, float *states, hipStream_t s)
+             const Plan &p, int B, int H, int n, int d, la_dtype dt, float *states, hipStream_t s,
+             const float *st_in = nullptr, float *st_out = nullptr)
 {
     const long scans = (long)B * H;
-    const ScanArgs a = make_args(A, Bm, C, Out, p, H, n, states, 0);
+    ScanArgs a = make_args(A, Bm, C, Out, p, H, n, states, 0);
+    a.st_in = st_in;
+    a.st_out = st_out;
     if (p.S > 1) {
         int rc = run_segment_states<REV>(a, lams, scans, d, dt, s);
         if (rc != LA_OK) return rc;
@@ -281,14 +287,16 @@ int la_plan(int B, int H, int n, int d, la_dtype dt, int *tile, int *segment_len
     return LA_OK;
 }
 
-int la_fwd(const void *Q, const void *K, const void *V, const float *lambda, void *O,
-           int B, int H, int n, int d, la_dtype dt,
-           void *workspace, size_t workspace_bytes, void *hip_stream)
+int la_fwd_state(const void *Q, const void *K, const void *V, const float *lambda, void *O,
+                 const float *kv_in, float *kv_out,
+                 int B, int H, int n, int d, la_dtype dt,
+                 void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     int rc = check_common(B, H, n, d, dt);
     if (rc != LA_OK) return rc;
     if (!Q || !K || !V || !O || !lambda) return LA_ERR_NULL;
-    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return LA_ERR_ALIGN;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) ||
+        !aligned16(kv_in) || !aligned16(kv_out)) return LA_ERR_ALIGN;
     LaLambdas lams;
     rc = check_lambda(lambda, H, &lams);
     if (rc != LA_OK) return rc;
@@ -297,7 +305,38 @@ int la_fwd(const void *Q, const void *K, const void *V, const float *lambda, voi
     if (rc != LA_OK) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
     // O = scan(Q, K, V)                                                   (Alg. 5)
-    return run_scan<false>(Q, K, V, O, lams, p, B, H, n, d, dt, (float *)workspace, s);
+    return run_scan<false>(Q, K, V, O, lams, p, B, H, n, d, dt, (float *)workspace, s, kv_in, kv_out);
+}
+
+int la_fwd(const void *Q, const void *K, const void *V, const float *lambda, void *O,
+           int B, int H, int n, int d, la_dtype dt,
+           void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return la_fwd_state(Q, K, V, lambda, O, nullptr, nullptr, B, H, n, d, dt,
+                        workspace, workspace_bytes, hip_stream);
+}
+
+int la_decode_step(const void *q, const void *k, const void *v, const float *lambda,
+                   float *kv, void *o, int B, int H, int d, la_dtype dt, void *hip_stream)
+{
+    int rc = check_common(B, H, 1, d, dt);
+    if (rc != LA_OK) return rc;
+    if (!q || !k || !v || !kv || !o || !lambda) return LA_ERR_NULL;
+    if (!aligned16(kv) || ((uintptr_t)q & 3u) || ((uintptr_t)k & 3u) || ((uintptr_t)v & 3u) ||
+        ((uintptr_t)o & 3u)) return LA_ERR_ALIGN;
+    LaLambdas lams;
+    rc = check_lambda(lambda, H, &lams);
+    if (rc != LA_OK) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    dim3 grid((unsigned)((long)B * H)), block(256);
+    if (dt == LA_BF16) {
+        if (d == 64) hipLaunchKernelGGL((la_decode_kernel<64, true>), grid, block, 0, s, q, k, v, kv, o, H, lams);
+        else hipLaunchKernelGGL((la_decode_kernel<128, true>), grid, block, 0, s, q, k, v, kv, o, H, lams);
+    } else {
+        if (d == 64) hipLaunchKernelGGL((la_decode_kernel<64, false>), grid, block, 0, s, q, k, v, kv, o, H, lams);
+        else hipLaunchKernelGGL((la_decode_kernel<128, false>), grid, block, 0, s, q, k, v, kv, o, H, lams);
+    }
+    return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 
 int la_bwd(const void *Q, const void *K, const void *V, const float *lambda, const void *dO,

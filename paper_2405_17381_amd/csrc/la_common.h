@@ -53,6 +53,9 @@ struct ScanArgs {
                          // 2^-skip_bits are not read (0 = read everything)
     int transpose_init;  // the stored segment states are those of the scan with Bm and C
                          // exchanged: read them transposed
+    const float *st_in;  // forward scans only: state carried in from earlier tokens,
+                         // [scans, D, D] fp32 (rows = Bm feature), or nullptr for zero
+    float *st_out;       // forward scans only: state after the last token, or nullptr
 };
 
 // One launch of the block-scan kernel runs one scan, or two scans that read
@@ -73,5 +76,6 @@ struct ScanLaunch {
 //   reverse: W[s] <- state entering segment s from the right (W[S-1] <- 0)
 struct SegScanArgs {
     float *states;       // [scans, S, DD]
+    const float *init;   // state entering the first (forward) segment, [scans, DD], or nullptr
     int H, S, L, DD;
 };

@@ -142,7 +142,8 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         int r = 4 * sa + i;
         wst[i] = REV ? pw(r) : pw(BK - 1 - r);
     }
-    const float lamBK = pw(BK);
+    float lamBK = pw(BK);
+    const bool want_final = !STATE_ONLY && !REV && a.st_out != nullptr && seg == a.S - 1;
     // row-major tiles: this thread's two 8-byte pieces of chunk sc
     const int nat_off = 16 * (sc >> 1) + 4 * (sc & 1);
     // transposed tiles, stores: feature f = 8sc + e lives in physical row
@@ -179,7 +180,9 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
 
     // ---- running state: St[i][j], j in this wave's slice ----------------------
     f32x16_t st[MT_D];
-    const bool has_init = !STATE_ONLY && a.S > 1 && gSt != nullptr;
+    // entering state: the scanned segment states, or (one segment) the caller's carried state
+    if (!STATE_ONLY && !REV && a.S == 1 && a.st_in) gSt = const_cast<float *>(a.st_in) + (size_t)scan * (D * D);
+    const bool has_init = !STATE_ONLY && gSt != nullptr && (a.S > 1 || (!REV && a.st_in));
     if (has_init && a.transpose_init) {
         // The stored state is that of the scan with Bm and C exchanged: copy it to LDS
         // with coalesced 16-byte loads (the tiles' storage is still unused) and read it
@@ -293,6 +296,15 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         // in a register per address for the whole loop
         asm volatile("" : "+v"(tw_u), "+v"(tr_pg));
         if (STATE_ONLY) __syncthreads();        // previous block's readers of sBT / sCT are done
+        if (want_final && t0 + BK > seg_hi) {
+            // The state handed back must be the one after the last real token: in the
+            // final, partial block of m rows weight row r by lambda^(m-1-r) and decay the
+            // old state by lambda^m instead of padding the block out to BK rows.
+            const int m = seg_hi - t0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) wst[i] = pw(max(m - 1 - (4 * sa + i), 0));
+            lamBK = pw(m);
+        }
         stage_block(t0);
         __syncthreads();
         if (ib + 1 < nblk) load_block(REV ? blk - 1 : blk + 1);
@@ -441,13 +453,14 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         }
     }
 
-    if (STATE_ONLY) {
+    if (STATE_ONLY || want_final) {
+        float *dst = STATE_ONLY ? gSt : a.st_out + (size_t)scan * (D * D);
 #pragma unroll
         for (int mt = 0; mt < MT_D; ++mt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 int i = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
-                gSt[(size_t)i * D + 32 * w + l32] = st[mt][v];
+                dst[(size_t)i * D + 32 * w + l32] = st[mt][v];
             }
     }
 }

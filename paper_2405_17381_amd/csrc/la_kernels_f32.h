@@ -54,13 +54,15 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
     // lambda^k, k = 0..BK, evaluated in double then rounded once
     for (int k = tid; k <= BK; k += 256) sPw[k] = (float)pow((double)lam, (double)k);
     // initial state
-    const bool has_init = !STATE_ONLY && a.S > 1 && gSt != nullptr;
+    if (!STATE_ONLY && !REV && a.S == 1 && a.st_in) gSt = const_cast<float *>(a.st_in) + (size_t)scan * (D * D);
+    const bool has_init = !STATE_ONLY && gSt != nullptr && (a.S > 1 || (!REV && a.st_in));
+    const bool want_final = !STATE_ONLY && !REV && a.st_out != nullptr && seg == a.S - 1;
     for (int e = tid; e < D * D; e += 256) {
         int i = e / D, j = e % D;
         sKV[i * LD + j] = has_init ? (a.transpose_init ? gSt[j * D + i] : gSt[e]) : 0.0f;
     }
     __syncthreads();
-    const float lamBK = sPw[BK];
+    float lamBK = sPw[BK];
 
     int ib0 = 0;     // pre-pass: skip blocks whose decay weights are below 2^-skip_bits
     if (STATE_ONLY && a.skip_bits > 0.f && lam < 1.0f) {
@@ -160,6 +162,10 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
         }
 
         // ---- St <- lambda^BK St + sum_r w_r Bm[r] C[r]^T ----
+        // (when the final state is handed back, the last, partial block of m rows is
+        //  weighted lambda^(m-1-r) and decays the old state by lambda^m)
+        const int m_rows = (want_final && t0 + BK > seg_hi) ? seg_hi - t0 : BK;
+        if (m_rows < BK) lamBK = sPw[m_rows];
         {
             float up[CJ][CJ];
 #pragma unroll
@@ -167,7 +173,7 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
 #pragma unroll
                 for (int j = 0; j < CJ; ++j) up[i][j] = 0.f;
             for (int r = 0; r < BK; ++r) {
-                float w = REV ? sPw[r] : sPw[BK - 1 - r];
+                float w = REV ? sPw[r] : sPw[max(m_rows - 1 - r, 0)];
                 float bv[CJ], cv[CJ];
 #pragma unroll
                 for (int i = 0; i < CJ; ++i) bv[i] = w * sB[r * LD + ty + 16 * i];
@@ -189,10 +195,11 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
         __syncthreads();
     }
 
-    if (STATE_ONLY) {
+    if (STATE_ONLY || want_final) {
+        float *dst = STATE_ONLY ? gSt : a.st_out + (size_t)scan * (D * D);
         for (int e = tid; e < D * D; e += 256) {
             int i = e / D, j = e % D;
-            gSt[e] = sKV[i * LD + j];
+            dst[e] = sKV[i * LD + j];
         }
     }
 }
@@ -213,6 +220,7 @@ __global__ __launch_bounds__(256) void la_segment_scan(SegScanArgs a, LaLambdas 
     const float lamL = (float)pow((double)lam, (double)a.L);
     float *W = a.states + (size_t)scan * a.S * a.DD + e;
     float4 carry = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (!REV && a.init) carry = *(const float4 *)(a.init + (size_t)scan * a.DD + e);
     for (int i0 = 0; i0 < a.S; i0 += 8) {
         float4 loc[8];
 #pragma unroll
@@ -233,6 +241,59 @@ __global__ __launch_bounds__(256) void la_segment_scan(SegScanArgs a, LaLambdas 
                 carry.z = fmaf(lamL, carry.z, loc[u].z);
                 carry.w = fmaf(lamL, carry.w, loc[u].w);
             }
+        }
+    }
+}
+
+// One token of the recurrence for every (batch, head) (App. A, recurrence form):
+//     kv <- lambda kv + k v^T ,  o = q^T kv
+// kv: [scans, D, D] fp32, updated in place; q, k, v, o: [scans, D] in T (fp32 or
+// bf16 stored as uint16).  One workgroup per scan; HBM-bound on the 2 x 4 D^2
+// bytes of state it streams.  Thread layout: D/4 threads cover a state row with
+// 16-byte accesses, 1024/D row groups stride the rows; per-column partial sums
+// of q^T kv are combined through LDS in a fixed order (deterministic).
+template <int D, bool BF16>
+__global__ __launch_bounds__(256) void la_decode_kernel(const void *q_, const void *k_, const void *v_,
+                                                        float *kv, void *o_, int H, LaLambdas lams)
+{
+    constexpr int TPR = D / 4;            // threads per state row
+    constexpr int RG = 256 / TPR;         // row groups
+    __shared__ float sq[D], sk[D], sv[D];
+    __shared__ float part[RG][D];
+    const int scan = blockIdx.x, tid = threadIdx.x;
+    const float lam = lams.v[scan % H];
+    auto ld = [&](const void *p, int i) -> float {
+        if (BF16) return __uint_as_float((uint32_t)((const uint16_t *)p)[(size_t)scan * D + i] << 16);
+        return ((const float *)p)[(size_t)scan * D + i];
+    };
+    if (tid < D) { sq[tid] = ld(q_, tid); sk[tid] = ld(k_, tid); sv[tid] = ld(v_, tid); }
+    __syncthreads();
+    const int j4 = (tid % TPR) * 4, rg = tid / TPR;
+    float *base = kv + (size_t)scan * D * D;
+    const float4 vv = make_float4(sv[j4], sv[j4 + 1], sv[j4 + 2], sv[j4 + 3]);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int i = rg; i < D; i += RG) {
+        float4 x = *(const float4 *)(base + (size_t)i * D + j4);
+        const float ki = sk[i], qi = sq[i];
+        x.x = fmaf(lam, x.x, ki * vv.x); x.y = fmaf(lam, x.y, ki * vv.y);
+        x.z = fmaf(lam, x.z, ki * vv.z); x.w = fmaf(lam, x.w, ki * vv.w);
+        *(float4 *)(base + (size_t)i * D + j4) = x;
+        acc.x = fmaf(qi, x.x, acc.x); acc.y = fmaf(qi, x.y, acc.y);
+        acc.z = fmaf(qi, x.z, acc.z); acc.w = fmaf(qi, x.w, acc.w);
+    }
+    part[rg][j4] = acc.x; part[rg][j4 + 1] = acc.y; part[rg][j4 + 2] = acc.z; part[rg][j4 + 3] = acc.w;
+    __syncthreads();
+    if (tid < D) {
+        float s = 0.f;
+#pragma unroll
+        for (int r = 0; r < RG; ++r) s += part[r][tid];
+        if (BF16) {
+            uint32_t u = __float_as_uint(s);
+            u += 0x7fffu + ((u >> 16) & 1u);            // round to nearest even
+            ((uint16_t *)o_)[(size_t)scan * D + tid] = (uint16_t)(u >> 16);
+        } else {
+            ((float *)o_)[(size_t)scan * D + tid] = s;
         }
     }
 }

@@ -1,0 +1,82 @@
+"""GPU parity of the carried-state forward pass and of the decode step against
+the CPU oracle (token recurrence with a carried state, fp64)."""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2405_17381_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+@pytest.fixture(autouse=True)
+def _env(monkeypatch):
+    assert torch.cuda.is_available()
+    binding.load_library()
+    monkeypatch.delenv("LA_LSEG", raising=False)
+    yield
+    torch.cuda.synchronize()
+
+
+def _case(dtype, d, n, pieces, lseg):
+    lam = [1.0, 0.999, 0.93, 0.4]
+    w = synth.custom(2, len(lam), n, d, lam, seed=4000 + n + d, dtype=dtype)
+    host = synth.draw(w)
+    tdt = TDT[dtype]
+    Q, K, V = [x.to(tdt).cuda() for x in host[:3]]
+    q, k, v = [x.to(tdt).to(torch.float64).numpy() for x in host[:3]]
+    O_ref, kv_ref = oracle.recurrence_fwd(q, k, v, lam, return_state=True)
+    if lseg:
+        os.environ["LA_LSEG"] = str(lseg)
+    try:
+        kv = torch.zeros(2, len(lam), d, d, dtype=torch.float32, device="cuda")
+        outs, pos = [], 0
+        for m in pieces:
+            sl = slice(pos, pos + m)
+            o = binding.la_fwd_state(Q[:, :, sl].contiguous(), K[:, :, sl].contiguous(),
+                                     V[:, :, sl].contiguous(), lam, kv_in=kv, kv_out=kv)
+            outs.append(o)
+            pos += m
+        assert pos == n
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("LA_LSEG", None)
+    O = torch.cat(outs, dim=2).to(torch.float64).cpu().numpy()
+    e_o = oracle.rel_max_err(O, O_ref)
+    e_s = oracle.rel_max_err(kv.double().cpu().numpy(), kv_ref)
+    print("  %s d%d n%d pieces=%s lseg=%s: O err %.3e, state err %.3e" % (dtype, d, n, pieces, lseg, e_o, e_s),
+          flush=True)
+    assert e_o <= TOL[dtype] and e_s <= TOL[dtype]
+    return Q, K, V, kv, lam, (q, k, v), kv_ref
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("f32", 128), ("bf16", 64), ("bf16", 128)])
+@pytest.mark.parametrize("n,pieces,lseg", [
+    (1000, [1000], None), (1000, [300, 64, 1, 635], None), (1000, [1000], 128),
+    (777, [500, 277], 64), (130, [65, 65], None),
+])
+def test_forward_with_carried_state(dtype, d, n, pieces, lseg):
+    _case(dtype, d, n, pieces, lseg)
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128), ("bf16", 64), ("f32", 128)])
+def test_decode_steps_after_prefill(dtype, d):
+    n = 200
+    Q, K, V, kv, lam, (q, k, v), kv_ref = _case(dtype, d, n, [n], None)
+    rng = np.random.default_rng(7)
+    tdt = TDT[dtype]
+    kv_o = kv_ref.copy()
+    for step in range(6):
+        xs = [torch.from_numpy(rng.standard_normal((2, len(lam), d)).astype(np.float32) / np.sqrt(d)).to(tdt)
+              for _ in range(3)]
+        o = binding.la_decode_step(xs[0].cuda(), xs[1].cuda(), xs[2].cuda(), lam, kv)
+        o_ref, kv_o = oracle.decode_step(*[x.to(torch.float64).numpy() for x in xs], lam, kv_o)
+        err = oracle.rel_max_err(o.to(torch.float64).cpu().numpy(), o_ref)
+        assert err <= TOL[dtype], (step, err)
+    assert oracle.rel_max_err(kv.double().cpu().numpy(), kv_o) <= TOL[dtype]
