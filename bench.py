@@ -186,6 +186,21 @@ def main():
                 "launches": launches, "avg_launch_ms": round(scan_ms / max(launches, 1), 5),
                 "algorithmic_bytes_per_launch": round(per_launch)}
 
+    # ---- what the memory system delivers for the same access shape, no arithmetic ----------
+    # torch.addcmul streams three 256 MiB bf16 tensors in and one out, like one block scan.
+    for _ in range(3):
+        torch.addcmul(flat["Q"], flat["K"], flat["V"], out=flat["O"])
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(10):
+        torch.addcmul(flat["Q"], flat["K"], flat["V"], out=flat["O"])
+    e1.record()
+    e1.synchronize()
+    stream_gbs = 4 * 2 * numel / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
+    roofline["measured_stream_GBps"] = round(stream_gbs, 1)
+    roofline["frac_of_measured_stream"] = round(achieved / stream_gbs, 4)
+
     # ---- decode step (next row after the training path): B=8, H=32, d=128, bf16 ----------
     # One token per (batch, head) streams the fp32 d x d state in and out: 2 * 4 d^2 bytes.
     dB, dH = 8, 32

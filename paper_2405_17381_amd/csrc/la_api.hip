@@ -10,6 +10,7 @@
 #include "la_common.h"
 #include "la_kernels_bf16.h"
 #include "la_kernels_f32.h"
+#include "la_kernels_misc.h"
 
 namespace {
 
