@@ -17,8 +17,8 @@ import subprocess
 
 import numpy as np
 
-from .la_oracle import (decay_matrix, decode_step, left_product_bwd, left_product_fwd,
-                        recurrence_bwd, recurrence_fwd, rel_max_err)
+from .la_oracle import (decay_matrix, decode_step, gate_norm_bwd, gate_norm_fwd, left_product_bwd,
+                        left_product_fwd, recurrence_bwd, recurrence_fwd, rel_max_err)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "la_oracle.c")

@@ -153,3 +153,30 @@ def rel_max_err(x, ref) -> float:
     if denom == 0.0:
         return float(np.max(np.abs(x)))
     return float(np.max(np.abs(x - ref)) / denom)
+
+
+# --------------------------------------------------------------------------
+# gated, normalised output of the attention block (Sec. 4.2, "Gating Mechanism"
+# and "Tensor Normalization"): Y = SRMSNorm(O) * U, SRMSNorm(x) = x / (||x||_2 / sqrt(D))
+# --------------------------------------------------------------------------
+def gate_norm_fwd(O, U, eps=0.0):
+    """O, U: [B, H, n, d].  The norm runs per token over all H*d features of
+    the attention output (the heads concatenated).  `eps` is added to the mean
+    square before the root; the paper's formula is eps = 0."""
+    O, U = _as64(O), _as64(U)
+    B, H, n, d = O.shape
+    ms = np.mean(O * O, axis=(1, 3), keepdims=True) + eps      # [B,1,n,1]
+    return O / np.sqrt(ms) * U
+
+
+def gate_norm_bwd(O, U, dY, eps=0.0):
+    """Gradients of Y = SRMSNorm(O) * U:  with r = sqrt(mean(O^2)+eps), N = O/r,
+    dN = dY*U:  dU = dY*N,  dO = dN/r - O * mean(dN*O) / r^3."""
+    O, U, dY = _as64(O), _as64(U), _as64(dY)
+    ms = np.mean(O * O, axis=(1, 3), keepdims=True) + eps
+    r = np.sqrt(ms)
+    dN = dY * U
+    dU = dY * O / r
+    c = np.mean(dN * O, axis=(1, 3), keepdims=True)
+    dO = dN / r - O * c / (r ** 3)
+    return dO, dU

@@ -288,3 +288,44 @@ def test_decode_steps_reproduce_the_sequence():
     g = load_golden("worked_example_a.txt")
     _, kv3 = oracle.recurrence_fwd(g["Q"], g["K"], g["V"], [g["lambda"]], return_state=True)
     assert abs(kv3[0, 0, 0, 0] - 7.25) < 1e-14
+
+
+# ---- 11. gated SRMSNorm output stage (Sec. 4.2) --------------------------------------
+def test_srmsnorm_worked_value_and_invariants():
+    # x = (3, 4), D = 2: ||x|| = 5, x / (5 / sqrt 2) = (3, 4) * sqrt(2) / 5
+    O = np.array([3.0, 4.0]).reshape(1, 1, 1, 2)
+    U = np.ones_like(O)
+    Y = oracle.gate_norm_fwd(O, U)
+    np.testing.assert_allclose(Y.ravel(), np.array([3.0, 4.0]) * np.sqrt(2.0) / 5.0, rtol=1e-15)
+    # heads are concatenated before the norm: two heads of one feature each give the same
+    Y2 = oracle.gate_norm_fwd(O.reshape(1, 2, 1, 1), np.ones((1, 2, 1, 1)))
+    np.testing.assert_allclose(Y2.ravel(), Y.ravel(), rtol=1e-15)
+    rng = np.random.default_rng(3)
+    O = rng.standard_normal((2, 3, 5, 4))
+    U = rng.standard_normal((2, 3, 5, 4))
+    N = oracle.gate_norm_fwd(O, np.ones_like(O))
+    np.testing.assert_allclose(np.mean(N * N, axis=(1, 3)), 1.0, rtol=1e-12)       # unit mean square
+    np.testing.assert_allclose(oracle.gate_norm_fwd(7.5 * O, U), oracle.gate_norm_fwd(O, U), rtol=1e-12)
+    np.testing.assert_allclose(oracle.gate_norm_fwd(O, U), N * U, rtol=1e-12)      # the gate is a plain product
+
+
+@pytest.mark.parametrize("eps", [0.0, 1e-3])
+def test_gate_norm_gradients_by_finite_differences(eps):
+    rng = np.random.default_rng(4)
+    O = rng.standard_normal((1, 2, 3, 4))
+    U = rng.standard_normal((1, 2, 3, 4))
+    dY = rng.standard_normal((1, 2, 3, 4))
+    dO, dU = oracle.gate_norm_bwd(O, U, dY, eps)
+    h = 1e-6
+    for which, grad in ((0, dO), (1, dU)):
+        for idx in np.ndindex(O.shape):
+            a = [O.copy(), U.copy()]
+            b = [O.copy(), U.copy()]
+            a[which][idx] += h
+            b[which][idx] -= h
+            fd = (np.sum(dY * oracle.gate_norm_fwd(a[0], a[1], eps)) -
+                  np.sum(dY * oracle.gate_norm_fwd(b[0], b[1], eps))) / (2 * h)
+            assert abs(fd - grad[idx]) <= 1e-7 * max(1.0, abs(grad[idx]))
+    if eps == 0.0:
+        # the normalised output does not change along O: <dO, O> = 0 per token
+        np.testing.assert_allclose(np.sum(dO * O, axis=(1, 3)), 0.0, atol=1e-12)
