@@ -226,6 +226,27 @@ def main():
               "achieved_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
               "note": "includes launch overhead of one small kernel per step; 32 MiB of state per step"}
 
+    # ---- gated SRMSNorm output stage (next row): same tensors as the (1, 65536) point ---------
+    tg = views(1, TOKENS)
+    def _time(fn, it=10):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(it):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / it
+    gf = _time(lambda: binding.la_gate_norm_fwd(tg["O"], tg["V"], 0.0, Y=tg["dQ"]))
+    gb = _time(lambda: binding.la_gate_norm_bwd(tg["O"], tg["V"], tg["dO"], 0.0, dO=tg["dK"], dU=tg["dV"]))
+    tensor_bytes = 2 * numel
+    gate_norm = {"workload": "Y = SRMSNorm(O) * U and its backward, [1,16,65536,128] bf16",
+                 "fwd_ms": round(gf, 4), "bwd_ms": round(gb, 4),
+                 "fwd_GBps": round(3 * tensor_bytes / (gf * 1e-3) / 1e9, 1),
+                 "bwd_GBps": round(5 * tensor_bytes / (gb * 1e-3) / 1e9, 1),
+                 "note": "algorithmic bytes: 3 tensors forward, 5 backward; HBM-bound"}
+
     total_tflops = value * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12
     out = {
         "metric": "fwd+bwd tokens/s (causal linear attention with decay, bf16, d=128, seq-len sweep "
@@ -243,6 +264,7 @@ def main():
         "sweep": sweep,
         "roofline": roofline,
         "decode": decode,
+        "gate_norm": gate_norm,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()

@@ -130,6 +130,28 @@ int la_decode_step(const void *q, const void *k, const void *v,
                    float *kv, void *o,
                    int B, int H, int d, la_dtype dt, void *hip_stream);
 
+/*
+ * Gated, normalised output stage of the attention block (Sec. 4.2, "Gating
+ * Mechanism" and "Tensor Normalization"), the step that follows la_fwd in the
+ * paper's GLA:
+ *     Y = SRMSNorm(O) * U ,   SRMSNorm(x) = x / sqrt(mean(x^2) + eps) ,
+ * the mean running, per token, over all H*d features of O (the heads
+ * concatenated); the paper's formula is eps = 0.  O, U: inputs, Y: output, all
+ * [B, H, n, d] of type dt (DEVICE); fp32 arithmetic inside.  eps must be finite
+ * and >= 0 (else LA_ERR_LAMBDA).  B <= 65535.  Needs no workspace.
+ */
+int la_gate_norm_fwd(const void *O, const void *U, void *Y, float eps,
+                     int B, int H, int n, int d, la_dtype dt, void *hip_stream);
+
+/*
+ * Backward of la_gate_norm_fwd: with r = sqrt(mean(O^2) + eps), dN = dY * U:
+ *     dU = dY * O / r ,   dO = dN / r - O * mean(dN * O) / r^3 .
+ * O, U, dY: inputs; dO, dU: outputs; all [B, H, n, d] of type dt (DEVICE).
+ * The dO written here is what la_bwd takes as its dO argument.
+ */
+int la_gate_norm_bwd(const void *O, const void *U, const void *dY, void *dO, void *dU, float eps,
+                     int B, int H, int n, int d, la_dtype dt, void *hip_stream);
+
 /* Static, human-readable text for an la_status value. */
 const char *la_strerror(int status);
 

@@ -15,7 +15,7 @@ import torch
 LA_F32, LA_BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libla.so")
-EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_fwd_state", "la_decode_step", "la_strerror", "la_plan",
+EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_fwd_state", "la_decode_step", "la_gate_norm_fwd", "la_gate_norm_bwd", "la_strerror", "la_plan",
            "la_profile_enable", "la_profile_collect")
 _lib = None
 
@@ -46,6 +46,11 @@ def load_library():
     lib.la_fwd_state.restype = ci
     lib.la_decode_step.argtypes = [vp, vp, vp, fp, vp, vp, ci, ci, ci, ci, vp]
     lib.la_decode_step.restype = ci
+    cf = ctypes.c_float
+    lib.la_gate_norm_fwd.argtypes = [vp, vp, vp, cf, ci, ci, ci, ci, ci, vp]
+    lib.la_gate_norm_fwd.restype = ci
+    lib.la_gate_norm_bwd.argtypes = [vp, vp, vp, vp, vp, cf, ci, ci, ci, ci, ci, vp]
+    lib.la_gate_norm_bwd.restype = ci
     lib.la_strerror.argtypes = [ci]
     lib.la_strerror.restype = ctypes.c_char_p
     ip = ctypes.POINTER(ci)
@@ -201,6 +206,37 @@ def la_bwd(Q, K, V, lam, dO, dQ=None, dK=None, dV=None, workspace: Optional[torc
     if rc != 0:
         raise LaError(rc, "la_bwd")
     return dQ, dK, dV
+
+
+def la_gate_norm_fwd(O, U, eps: float = 0.0, Y=None):
+    """Y = SRMSNorm(O) * U (norm per token over all heads and features)."""
+    _check([O, U])
+    B, H, n, d = O.shape
+    Y = torch.empty_like(O) if Y is None else Y
+    _check([O, Y])
+    with torch.cuda.device(O.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_gate_norm_fwd(O.data_ptr(), U.data_ptr(), Y.data_ptr(), float(eps),
+                                             B, H, n, d, _dt(O), stream)
+    if rc != 0:
+        raise LaError(rc, "la_gate_norm_fwd")
+    return Y
+
+
+def la_gate_norm_bwd(O, U, dY, eps: float = 0.0, dO=None, dU=None):
+    """(dO, dU) of Y = SRMSNorm(O) * U."""
+    _check([O, U, dY])
+    B, H, n, d = O.shape
+    dO = torch.empty_like(O) if dO is None else dO
+    dU = torch.empty_like(O) if dU is None else dU
+    _check([O, dO, dU])
+    with torch.cuda.device(O.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_gate_norm_bwd(O.data_ptr(), U.data_ptr(), dY.data_ptr(), dO.data_ptr(),
+                                             dU.data_ptr(), float(eps), B, H, n, d, _dt(O), stream)
+    if rc != 0:
+        raise LaError(rc, "la_gate_norm_bwd")
+    return dO, dU
 
 
 def la_profile_enable(on: bool) -> None:

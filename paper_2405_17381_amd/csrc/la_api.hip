@@ -10,6 +10,7 @@
 #include "la_common.h"
 #include "la_kernels_bf16.h"
 #include "la_kernels_f32.h"
+#include "la_kernels_gate.h"
 #include "la_kernels_misc.h"
 
 namespace {
@@ -266,6 +267,20 @@ int check_workspace(const Plan &p, int B, int H, int d, void *workspace, size_t 
     return LA_OK;
 }
 
+template <bool BWD>
+int run_gate_norm(const GateArgs &g, int B, int n, int d, la_dtype dt, hipStream_t s)
+{
+    dim3 grid((unsigned)((n + 7) / 8), (unsigned)B), block(256);
+    if (dt == LA_BF16) {
+        if (d == 64) hipLaunchKernelGGL((la_gate_norm_kernel<64, true, BWD>), grid, block, 0, s, g);
+        else hipLaunchKernelGGL((la_gate_norm_kernel<128, true, BWD>), grid, block, 0, s, g);
+    } else {
+        if (d == 64) hipLaunchKernelGGL((la_gate_norm_kernel<64, false, BWD>), grid, block, 0, s, g);
+        else hipLaunchKernelGGL((la_gate_norm_kernel<128, false, BWD>), grid, block, 0, s, g);
+    }
+    return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
@@ -365,6 +380,37 @@ int la_bwd(const void *Q, const void *K, const void *V, const float *lambda, con
     return run_reverse_pair(Q, K, V, dO, dK, dV, lams, p, B, H, n, d, dt, ws, s);
 }
 
+int la_gate_norm_fwd(const void *O, const void *U, void *Y, float eps,
+                     int B, int H, int n, int d, la_dtype dt, void *hip_stream)
+{
+    int rc = check_common(B, H, n, d, dt);
+    if (rc != LA_OK) return rc;
+    if (B > 65535) return LA_ERR_SHAPE;
+    if (!O || !U || !Y) return LA_ERR_NULL;
+    if (!aligned16(O) || !aligned16(U) || !aligned16(Y)) return LA_ERR_ALIGN;
+    if (!(eps >= 0.0f) || !std::isfinite(eps)) return LA_ERR_LAMBDA;
+    GateArgs g;
+    g.O = O; g.U = U; g.dY = nullptr; g.Y = Y; g.dO = nullptr; g.dU = nullptr;
+    g.H = H; g.n = n; g.eps = eps;
+    return run_gate_norm<false>(g, B, n, d, dt, (hipStream_t)hip_stream);
+}
+
+int la_gate_norm_bwd(const void *O, const void *U, const void *dY, void *dO, void *dU, float eps,
+                     int B, int H, int n, int d, la_dtype dt, void *hip_stream)
+{
+    int rc = check_common(B, H, n, d, dt);
+    if (rc != LA_OK) return rc;
+    if (B > 65535) return LA_ERR_SHAPE;
+    if (!O || !U || !dY || !dO || !dU) return LA_ERR_NULL;
+    if (!aligned16(O) || !aligned16(U) || !aligned16(dY) || !aligned16(dO) || !aligned16(dU))
+        return LA_ERR_ALIGN;
+    if (!(eps >= 0.0f) || !std::isfinite(eps)) return LA_ERR_LAMBDA;
+    GateArgs g;
+    g.O = O; g.U = U; g.dY = dY; g.Y = nullptr; g.dO = dO; g.dU = dU;
+    g.H = H; g.n = n; g.eps = eps;
+    return run_gate_norm<true>(g, B, n, d, dt, (hipStream_t)hip_stream);
+}
+
 const char *la_strerror(int status)
 {
     switch (status) {
@@ -372,7 +418,7 @@ const char *la_strerror(int status)
     case LA_ERR_NULL: return "a required pointer is NULL";
     case LA_ERR_SHAPE: return "invalid shape: need B,H,n >= 1, H <= 256, d in {64,128}";
     case LA_ERR_DTYPE: return "invalid dtype";
-    case LA_ERR_LAMBDA: return "decay rate not finite or outside (0, 1]";
+    case LA_ERR_LAMBDA: return "decay rate not finite or outside (0, 1] (or eps negative / not finite)";
     case LA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case LA_ERR_LAUNCH: return "HIP kernel launch failed";
     case LA_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
