@@ -71,7 +71,8 @@ typedef enum {
  * needs for this problem size.  The scratch holds the d x d fp32 states at
  * segment boundaries when a sequence is cut into segments so that a small
  * B*H still fills the GPU (the block recurrence of App. C, "KV_t" and
- * "dKV_t", applied at segment instead of block granularity).  Returns 0 when
+ * "dKV_t", applied at segment instead of block granularity); la_bwd needs twice
+ * what la_fwd needs.  Returns 0 when
  * no scratch is needed or when the arguments are invalid.  Pure host
  * arithmetic: callable without a GPU.
  */

@@ -84,6 +84,14 @@ int check_lambda(const float *lambda, int H, LaLambdas *out)
         out->lg2[h] = (float)std::log2((double)l);
     }
     for (int h = H; h < LA_MAX_HEADS; ++h) { out->v[h] = 1.0f; out->lg2[h] = 0.0f; }
+    // heads by decreasing lambda (stable): insertion sort, H <= 256
+    for (int h = 0; h < LA_MAX_HEADS; ++h) out->order[h] = (uint8_t)h;
+    for (int i = 1; i < H; ++i) {
+        const uint8_t x = out->order[i];
+        int j = i - 1;
+        while (j >= 0 && out->v[out->order[j]] < out->v[x]) { out->order[j + 1] = out->order[j]; --j; }
+        out->order[j + 1] = x;
+    }
     return LA_OK;
 }
 
@@ -154,7 +162,7 @@ hipError_t launch_f32(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
     if (attr_err != hipSuccess) return attr_err;
-    dim3 grid((unsigned)a.items), block(Cfg::NT);    // the fp32 path never pairs
+    dim3 grid((unsigned)(a.items * a.nroles)), block(Cfg::NT);   // roles one after the other
     hipLaunchKernelGGL(kern, grid, block, Cfg::lds_bytes, s, a, lams);
     return hipGetLastError();
 }
@@ -178,24 +186,32 @@ ScanArgs make_args(const void *A, const void *Bm, const void *C, void *Out, cons
     a.A = A; a.Bm = Bm; a.C = C; a.Out = Out;
     a.states = p.S > 1 ? states : nullptr;
     a.n = n; a.H = H; a.L = p.L; a.S = p.S;
+    a.B = 0;             // set by the callers that launch a pre-pass
     a.transpose_init = transpose_init;
     // Pre-pass cut-off: 2^-48 of the nearest row's weight, far below the 2^-24
     // resolution of the fp32 state it is added to (LA_NO_DECAY_SKIP reads everything).
     a.skip_bits = std::getenv("LA_NO_DECAY_SKIP") ? 0.0f : 48.0f;
+    a.rev = 0;
     a.st_in = nullptr;
     a.st_out = nullptr;
     return a;
 }
 
-// Segment-boundary states of scan(., Bm, C): local states per segment, then the
-// exclusive scan over segments, in place in `states`.
-template <bool REV>
-int run_segment_states(const ScanArgs &a, const LaLambdas &lams, long scans, int d, la_dtype dt,
-                       hipStream_t s)
+// Segment-state pre-pass: the local end state of every segment of scan(., Bm, C),
+// for one scan or, in one launch, for two independent scans (their short, latency-
+// bound chains then fill the machine together).
+int run_prepass(const ScanArgs *a, int nroles, const LaLambdas &lams, long scans, int d, la_dtype dt,
+                hipStream_t s)
 {
     ScanLaunch l;
-    l.r[0] = a; l.r[1] = a; l.nroles = 1; l.items = (int)(scans * a.S);
-    if (launch_scan_kernel<REV, true>(l, lams, d, dt, s) != hipSuccess) return LA_ERR_LAUNCH;
+    l.r[0] = a[0]; l.r[1] = a[nroles - 1]; l.nroles = nroles; l.items = (int)(scans * a[0].S);
+    return launch_scan_kernel<false, true>(l, lams, d, dt, s) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+// Exclusive scan over the segments, in place: local states -> entering states.
+template <bool REV>
+int run_segment_scan(const ScanArgs &a, const LaLambdas &lams, long scans, int d, hipStream_t s)
+{
     SegScanArgs sa;
     sa.states = a.states; sa.init = REV ? nullptr : a.st_in;
     sa.H = a.H; sa.S = a.S; sa.L = a.L; sa.DD = d * d;
@@ -204,7 +220,16 @@ int run_segment_states(const ScanArgs &a, const LaLambdas &lams, long scans, int
     return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 
-// One decayed causal scan Out = scan(A, Bm, C): [segment states ->] block scan.
+template <bool REV>
+int run_block_scan(const ScanArgs &a, const LaLambdas &lams, long scans, int d, la_dtype dt, hipStream_t s)
+{
+    ScanLaunch l;
+    l.r[0] = a; l.r[1] = a; l.nroles = 1; l.items = (int)(scans * a.S);
+    ScopedTimer t(s);
+    return launch_scan_kernel<REV, false>(l, lams, d, dt, s) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+// One decayed causal scan Out = scan(A, Bm, C): [pre-pass -> segment scan ->] block scan.
 template <bool REV>
 int run_scan(const void *A, const void *Bm, const void *C, void *Out, const LaLambdas &lams,
              const Plan &p, int B, int H, int n, int d, la_dtype dt, float *states, hipStream_t s,
@@ -212,16 +237,16 @@ int run_scan(const void *A, const void *Bm, const void *C, void *Out, const LaLa
 {
     const long scans = (long)B * H;
     ScanArgs a = make_args(A, Bm, C, Out, p, H, n, states, 0);
+    a.B = B;
+    a.rev = REV ? 1 : 0;
     a.st_in = st_in;
     a.st_out = st_out;
     if (p.S > 1) {
-        int rc = run_segment_states<REV>(a, lams, scans, d, dt, s);
+        int rc = run_prepass(&a, 1, lams, scans, d, dt, s);
+        if (rc == LA_OK) rc = run_segment_scan<REV>(a, lams, scans, d, s);
         if (rc != LA_OK) return rc;
     }
-    ScanLaunch l;
-    l.r[0] = a; l.r[1] = a; l.nroles = 1; l.items = (int)(scans * p.S);
-    ScopedTimer t(s);
-    return launch_scan_kernel<REV, false>(l, lams, d, dt, s) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+    return run_block_scan<REV>(a, lams, scans, d, dt, s);
 }
 
 // The two reverse scans of Alg. 6's second loop,
@@ -230,37 +255,55 @@ int run_scan(const void *A, const void *Bm, const void *C, void *Out, const LaLa
 // share one set of segment states (dV reads dK's transposed) and, on the bf16
 // path, one paired launch in which the two workgroups of a segment sit on the
 // same XCD, so that dO and Q, which both read, come from HBM once.
-int run_reverse_pair(const void *Q, const void *K, const void *V, const void *dO, void *dK, void *dV,
-                     const LaLambdas &lams, const Plan &p, int B, int H, int n, int d, la_dtype dt,
-                     float *states, hipStream_t s)
+int run_reverse_pair(const ScanArgs &ak, const ScanArgs &av, const LaLambdas &lams, long scans,
+                     int d, la_dtype dt, hipStream_t s)
 {
-    const long scans = (long)B * H;
-    const ScanArgs ak = make_args(V, dO, Q, dK, p, H, n, states, 0);
-    const ScanArgs av = make_args(K, Q, dO, dV, p, H, n, states, 1);
-    if (p.S > 1) {
-        int rc = run_segment_states<true>(ak, lams, scans, d, dt, s);
-        if (rc != LA_OK) return rc;
-    }
     ScanLaunch l;
-    l.items = (int)(scans * p.S);
+    l.items = (int)(scans * ak.S);
     const bool pair = dt == LA_BF16 && std::getenv("LA_NO_PAIR") == nullptr;
     if (pair) {
         l.r[0] = ak; l.r[1] = av; l.nroles = 2;
         ScopedTimer t(s);
         return launch_scan_kernel<true, false>(l, lams, d, dt, s) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
     }
-    l.nroles = 1;
-    for (int i = 0; i < 2; ++i) {
-        l.r[0] = i == 0 ? ak : av; l.r[1] = l.r[0];
-        ScopedTimer t(s);
-        if (launch_scan_kernel<true, false>(l, lams, d, dt, s) != hipSuccess) return LA_ERR_LAUNCH;
-    }
-    return LA_OK;
+    int rc = run_block_scan<true>(ak, lams, scans, d, dt, s);
+    if (rc != LA_OK) return rc;
+    return run_block_scan<true>(av, lams, scans, d, dt, s);
 }
 
-int check_workspace(const Plan &p, int B, int H, int d, void *workspace, size_t workspace_bytes)
+// Backward pass.  dQ = scan(dO, V, K) is the first loop of Alg. 6 (state KV^T); the
+// second loop is the reverse pair above.  With segments, the two pre-passes (forward
+// states of (V, K), reverse states of (dO, Q)) run as one launch into the two halves
+// of the scratch, then the two segment scans, then the block scans.
+int run_backward(const void *Q, const void *K, const void *V, const void *dO, void *dQ, void *dK,
+                 void *dV, const LaLambdas &lams, const Plan &p, int B, int H, int n, int d,
+                 la_dtype dt, float *ws, hipStream_t s)
 {
-    const size_t need = state_bytes(p, B, H, d);
+    const long scans = (long)B * H;
+    float *ws_f = ws;
+    float *ws_r = ws ? ws + (size_t)scans * p.S * (size_t)d * d : nullptr;
+    ScanArgs pre[2];
+    pre[0] = make_args(dO, V, K, dQ, p, H, n, ws_f, 0);
+    pre[1] = make_args(V, dO, Q, dK, p, H, n, ws_r, 0);
+    pre[1].rev = 1;
+    pre[0].B = pre[1].B = B;
+    ScanArgs av = make_args(K, Q, dO, dV, p, H, n, ws_r, 1);
+    av.rev = 1;
+    if (p.S > 1) {
+        int rc = run_prepass(pre, 2, lams, scans, d, dt, s);
+        if (rc == LA_OK) rc = run_segment_scan<false>(pre[0], lams, scans, d, s);
+        if (rc == LA_OK) rc = run_segment_scan<true>(pre[1], lams, scans, d, s);
+        if (rc != LA_OK) return rc;
+    }
+    int rc = run_block_scan<false>(pre[0], lams, scans, d, dt, s);
+    if (rc != LA_OK) return rc;
+    return run_reverse_pair(pre[1], av, lams, scans, d, dt, s);
+}
+
+int check_workspace(const Plan &p, int B, int H, int d, void *workspace, size_t workspace_bytes,
+                    bool is_bwd)
+{
+    const size_t need = state_bytes(p, B, H, d) * (is_bwd ? 2 : 1);
     if (need == 0) return LA_OK;
     if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < need)
         return LA_ERR_WORKSPACE;
@@ -287,9 +330,9 @@ extern "C" {
 
 size_t la_workspace_bytes(int B, int H, int n, int d, la_dtype dt, int is_bwd)
 {
-    (void)is_bwd;   // the three backward scans run one after another and share the scratch
+    // backward: forward states of (V, K) and reverse states of (dO, Q) side by side
     if (check_common(B, H, n, d, dt) != LA_OK) return 0;
-    return state_bytes(make_plan(B, H, n, d, dt), B, H, d);
+    return state_bytes(make_plan(B, H, n, d, dt), B, H, d) * (is_bwd ? 2 : 1);
 }
 
 int la_plan(int B, int H, int n, int d, la_dtype dt, int *tile, int *segment_len, int *segments)
@@ -317,7 +360,7 @@ int la_fwd_state(const void *Q, const void *K, const void *V, const float *lambd
     rc = check_lambda(lambda, H, &lams);
     if (rc != LA_OK) return rc;
     const Plan p = make_plan(B, H, n, d, dt);
-    rc = check_workspace(p, B, H, d, workspace, workspace_bytes);
+    rc = check_workspace(p, B, H, d, workspace, workspace_bytes, false);
     if (rc != LA_OK) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
     // O = scan(Q, K, V)                                                   (Alg. 5)
@@ -369,15 +412,10 @@ int la_bwd(const void *Q, const void *K, const void *V, const float *lambda, con
     rc = check_lambda(lambda, H, &lams);
     if (rc != LA_OK) return rc;
     const Plan p = make_plan(B, H, n, d, dt);
-    rc = check_workspace(p, B, H, d, workspace, workspace_bytes);
+    rc = check_workspace(p, B, H, d, workspace, workspace_bytes, true);
     if (rc != LA_OK) return rc;
-    hipStream_t s = (hipStream_t)hip_stream;
-    float *ws = (float *)workspace;
-    // dQ = scan(dO, V, K): first loop of Alg. 6, state = KV^T
-    rc = run_scan<false>(dO, V, K, dQ, lams, p, B, H, n, d, dt, ws, s);
-    if (rc != LA_OK) return rc;
-    // dK = scan_rev(V, dO, Q) and dV = scan_rev(K, Q, dO): second loop of Alg. 6
-    return run_reverse_pair(Q, K, V, dO, dK, dV, lams, p, B, H, n, d, dt, ws, s);
+    return run_backward(Q, K, V, dO, dQ, dK, dV, lams, p, B, H, n, d, dt, (float *)workspace,
+                        (hipStream_t)hip_stream);
 }
 
 int la_gate_norm_fwd(const void *O, const void *U, void *Y, float eps,

@@ -37,6 +37,8 @@
 struct LaLambdas {
     float v[LA_MAX_HEADS];      // lambda_h
     float lg2[LA_MAX_HEADS];    // log2(lambda_h), evaluated in double on the host
+    uint8_t order[LA_MAX_HEADS]; // heads by decreasing lambda: the pre-pass dispatches the
+                                // slowly decaying heads (longest chains) first
 };
 
 struct ScanArgs {
@@ -49,10 +51,13 @@ struct ScanArgs {
     int H;               // heads (scan index % H selects lambda)
     int L;               // segment length in tokens (multiple of the tile length)
     int S;               // segments per scan
+    int B;               // batch size (scan index = b * H + h)
     float skip_bits;     // segment-state pre-pass only: rows whose decay weight is below
                          // 2^-skip_bits are not read (0 = read everything)
     int transpose_init;  // the stored segment states are those of the scan with Bm and C
                          // exchanged: read them transposed
+    int rev;             // segment-state pre-pass only: direction of this role's scan
+                         // (block scans take the direction from the kernel's template)
     const float *st_in;  // forward scans only: state carried in from earlier tokens,
                          // [scans, D, D] fp32 (rows = Bm feature), or nullptr for zero
     float *st_out;       // forward scans only: state after the last token, or nullptr

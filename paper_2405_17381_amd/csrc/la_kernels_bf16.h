@@ -116,10 +116,18 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
     }
     const ScanArgs &a = launch.r[role];
     const int seg = item % a.S;
-    const int scan = item / a.S;
+    int scan = item / a.S;
     if (STATE_ONLY) {
-        if (!REV && seg == a.S - 1) return;    // never consumed
-        if (REV && seg == 0) return;
+        // pre-pass: items run over (head in dispatch order, batch, segment)
+        const int b = scan % a.B, hi = scan / a.B;
+        scan = b * a.H + lams.order[hi];
+    }
+    // The pre-pass takes its direction per role at run time (one launch can hold a
+    // forward and a reverse pre-pass); the block scans take it from the template.
+    const bool rev = STATE_ONLY ? (a.rev != 0) : REV;
+    if (STATE_ONLY) {
+        if (!rev && seg == a.S - 1) return;    // never consumed
+        if (rev && seg == 0) return;
     }
     const float lg = lams.lg2[scan % a.H];
     auto pw = [lg](int k) -> float { return exp2f((float)k * lg); };
@@ -140,7 +148,7 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int r = 4 * sa + i;
-        wst[i] = REV ? pw(r) : pw(BK - 1 - r);
+        wst[i] = rev ? pw(r) : pw(BK - 1 - r);
     }
     float lamBK = pw(BK);
     const bool want_final = !STATE_ONLY && !REV && a.st_out != nullptr && seg == a.S - 1;
@@ -287,10 +295,10 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         if (reach < (float)(nblk * BK)) ib0 = max(0, nblk - ((int)(reach / BK) + 2));
     }
 
-    load_block(REV ? nblk - 1 - ib0 : ib0);
+    load_block(rev ? nblk - 1 - ib0 : ib0);
 
     for (int ib = ib0; ib < nblk; ++ib) {
-        const int blk = REV ? (nblk - 1 - ib) : ib;
+        const int blk = rev ? (nblk - 1 - ib) : ib;
         const int t0 = seg_lo + blk * BK;
         // the swizzle terms are re-derived per block (one XOR each) instead of living
         // in a register per address for the whole loop
@@ -307,7 +315,7 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         }
         stage_block(t0);
         __syncthreads();
-        if (ib + 1 < nblk) load_block(REV ? blk - 1 : blk + 1);
+        if (ib + 1 < nblk) load_block(rev ? blk - 1 : blk + 1);
 
         U4 cf[KS_B];                            // C^T fragments of this wave's slice
         auto load_cf = [&]() {

@@ -19,7 +19,10 @@ struct F32Cfg {
 template <int D, int BK, bool REV, bool STATE_ONLY>
 __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas lams)
 {
-    const ScanArgs &a = launch.r[0];
+    // two roles (two independent pre-passes in one launch) follow one another in the grid
+    const int role = launch.nroles == 2 ? (int)(blockIdx.x / launch.items) : 0;
+    const int item = launch.nroles == 2 ? (int)(blockIdx.x % launch.items) : (int)blockIdx.x;
+    const ScanArgs &a = launch.r[role];
     using Cfg = F32Cfg<D, BK>;
     constexpr int LD = Cfg::LD, LS = Cfg::LS, RI = Cfg::RI, CJ = Cfg::CJ;
     extern __shared__ float smem_f32[];
@@ -32,16 +35,21 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
 
     const int tid = threadIdx.x;
     const int ty = tid >> 4, tx = tid & 15;
-    const int seg = blockIdx.x % a.S;
-    const int scan = blockIdx.x / a.S;
+    const int seg = item % a.S;
+    int scan = item / a.S;
+    if (STATE_ONLY) {
+        const int b = scan % a.B, hi = scan / a.B;
+        scan = b * a.H + lams.order[hi];
+    }
     const float lam = lams.v[scan % a.H];
 
     const int seg_lo = seg * a.L;
     const int seg_hi = min(a.n, seg_lo + a.L);
+    const bool rev = STATE_ONLY ? (a.rev != 0) : REV;
     if (STATE_ONLY) {
         // the state leaving the last (forward) / first (reverse) segment is never used
-        if (!REV && seg == a.S - 1) return;
-        if (REV && seg == 0) return;
+        if (!rev && seg == a.S - 1) return;
+        if (rev && seg == 0) return;
     }
     const int nblk = (seg_hi - seg_lo + BK - 1) / BK;
 
@@ -70,7 +78,7 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
         if (reach < (float)(nblk * BK)) ib0 = max(0, nblk - ((int)(reach / BK) + 2));
     }
     for (int ib = ib0; ib < nblk; ++ib) {
-        const int blk = REV ? (nblk - 1 - ib) : ib;
+        const int blk = rev ? (nblk - 1 - ib) : ib;
         const int t0 = seg_lo + blk * BK;
         // ---- load tiles (rows past the segment end are zero) ----
         for (int e = tid; e < BK * (D / 4); e += 256) {
@@ -173,7 +181,7 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
 #pragma unroll
                 for (int j = 0; j < CJ; ++j) up[i][j] = 0.f;
             for (int r = 0; r < BK; ++r) {
-                float w = REV ? sPw[r] : sPw[max(m_rows - 1 - r, 0)];
+                float w = rev ? sPw[r] : sPw[max(m_rows - 1 - r, 0)];
                 float bv[CJ], cv[CJ];
 #pragma unroll
                 for (int i = 0; i < CJ; ++i) bv[i] = w * sB[r * LD + ty + 16 * i];

@@ -41,8 +41,10 @@ def test_plan_and_workspace(monkeypatch):
     # few scans, long sequence: segmented, scratch = scans * S * d*d * 4
     tile, L, S = binding.la_plan(1, 16, 65536, 128, binding.LA_BF16)
     assert S > 1 and L % tile == 0 and (S - 1) * L < 65536 <= S * L
-    need = binding.la_workspace_bytes(1, 16, 65536, 128, binding.LA_BF16, True)
+    need = binding.la_workspace_bytes(1, 16, 65536, 128, binding.LA_BF16, False)
     assert need == 16 * S * 128 * 128 * 4
+    # backward keeps forward states of (V,K) and reverse states of (dO,Q) side by side
+    assert binding.la_workspace_bytes(1, 16, 65536, 128, binding.LA_BF16, True) == 2 * need
     # fp32 tile lengths
     assert binding.la_plan(1, 2, 256, 64, binding.LA_F32)[0] == 64
     assert binding.la_plan(1, 2, 256, 128, binding.LA_F32)[0] == 32
