@@ -249,3 +249,22 @@ def test_c4_silu_features_sampled():
 def test_c5_long_context_sampled():
     # heads with lambda = 1 (no decay over 2048 blocks) and the slowest decay
     _sampled_case(synth.workload("c5"), [(0, 0), (0, 31)], slabwise=True)
+
+
+# ---- planner and limits --------------------------------------------------------------------
+def test_maximum_head_count():
+    H = 256
+    lam = [float(0.5 + 0.5 * (h / (H - 1))) for h in range(H)]          # 0.5 .. 1.0
+    w = synth.custom(1, H, 130, 64, lam, seed=321, dtype="bf16")
+    _full_case(w)
+
+
+@pytest.mark.parametrize("dtype,d,n", [("bf16", 128, 5000), ("f32", 64, 3000)])
+def test_planner_segments_a_small_batch_by_itself(dtype, d, n):
+    """Few scans: the planner cuts the sequences without any override."""
+    lam = [1.0, 0.995, 0.9]
+    dt = binding.LA_BF16 if dtype == "bf16" else binding.LA_F32
+    tile, L, S = binding.la_plan(1, 3, n, d, dt)
+    assert S > 1 and L >= 512
+    w = synth.custom(1, 3, n, d, lam, seed=654 + n, dtype=dtype)
+    _full_case(w)
