@@ -12,6 +12,7 @@
 #include "la_kernels_f32.h"
 #include "la_kernels_gate.h"
 #include "la_kernels_misc.h"
+#include "la_kernels_prepass.h"
 
 namespace {
 
@@ -137,11 +138,11 @@ hipError_t allow_lds(K kernel, size_t bytes)
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-template <int D, bool REV, bool STATE_ONLY>
+template <int D, bool REV>
 hipError_t launch_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
     using Cfg = Bf16Cfg<D>;
-    auto kern = la_scan_bf16<D, REV, STATE_ONLY>;
+    auto kern = la_scan_bf16<D, REV>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
@@ -149,6 +150,20 @@ hipError_t launch_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s
     // paired launch: two workgroups per item, items padded to a multiple of the 8 XCDs
     const unsigned wgs = a.nroles == 2 ? 2u * (unsigned)((a.items + 7) / 8 * 8) : (unsigned)a.items;
     dim3 grid(wgs), block(Cfg::NT);
+    hipLaunchKernelGGL(kern, grid, block, Cfg::lds_bytes, s, a, lams);
+    return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_prepass_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
+{
+    using Cfg = PrepassCfg<D>;
+    auto kern = la_prepass_bf16<D>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
+    if (attr_err != hipSuccess) return attr_err;
+    dim3 grid((unsigned)(a.items * a.nroles)), block(Cfg::NT);
     hipLaunchKernelGGL(kern, grid, block, Cfg::lds_bytes, s, a, lams);
     return hipGetLastError();
 }
@@ -172,8 +187,9 @@ hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
                               la_dtype dt, hipStream_t s)
 {
     if (dt == LA_BF16) {
-        if (d == 64) return launch_bf16<64, REV, STATE_ONLY>(a, lams, s);
-        return launch_bf16<128, REV, STATE_ONLY>(a, lams, s);
+        if (STATE_ONLY) return d == 64 ? launch_prepass_bf16<64>(a, lams, s) : launch_prepass_bf16<128>(a, lams, s);
+        if (d == 64) return launch_bf16<64, REV>(a, lams, s);
+        return launch_bf16<128, REV>(a, lams, s);
     }
     if (d == 64) return launch_f32<64, 64, REV, STATE_ONLY>(a, lams, s);
     return launch_f32<128, 32, REV, STATE_ONLY>(a, lams, s);

@@ -1,4 +1,6 @@
 // bf16 path: the block loop of Alg. 5 / Alg. 6 on gfx950 matrix cores.
+// (The segment-state pre-pass that lets one scan be cut into segments is in
+// la_kernels_prepass.h and reuses the tile layouts and helpers defined here.)
 //
 // One workgroup of D/32 wavefronts walks the blocks (BK = 64 rows) of one
 // segment of one (batch, head) scan.  All four contractions of a block run on
@@ -83,7 +85,7 @@ struct Bf16Cfg {
     static constexpr size_t lds_bytes = 2 * (size_t)(nA + nB + nBT + nCT + nP);
 };
 
-template <int D, bool REV, bool STATE_ONLY>
+template <int D, bool REV>
 __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLambdas lams)
 {
     using Cfg = Bf16Cfg<D>;
@@ -116,19 +118,8 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
     }
     const ScanArgs &a = launch.r[role];
     const int seg = item % a.S;
-    int scan = item / a.S;
-    if (STATE_ONLY) {
-        // pre-pass: items run over (head in dispatch order, batch, segment)
-        const int b = scan % a.B, hi = scan / a.B;
-        scan = b * a.H + lams.order[hi];
-    }
-    // The pre-pass takes its direction per role at run time (one launch can hold a
-    // forward and a reverse pre-pass); the block scans take it from the template.
-    const bool rev = STATE_ONLY ? (a.rev != 0) : REV;
-    if (STATE_ONLY) {
-        if (!rev && seg == a.S - 1) return;    // never consumed
-        if (rev && seg == 0) return;
-    }
+    const int scan = item / a.S;
+    constexpr bool rev = REV;
     const float lg = lams.lg2[scan % a.H];
     auto pw = [lg](int k) -> float { return exp2f((float)k * lg); };
 
@@ -151,7 +142,7 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         wst[i] = rev ? pw(r) : pw(BK - 1 - r);
     }
     float lamBK = pw(BK);
-    const bool want_final = !STATE_ONLY && !REV && a.st_out != nullptr && seg == a.S - 1;
+    const bool want_final = !REV && a.st_out != nullptr && seg == a.S - 1;
     // row-major tiles: this thread's two 8-byte pieces of chunk sc
     const int nat_off = 16 * (sc >> 1) + 4 * (sc & 1);
     // transposed tiles, stores: feature f = 8sc + e lives in physical row
@@ -165,7 +156,7 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
 
     float rsq[2];                              // inter-block scale of column q = 32mt + l32
     float mk[NTILE][16];                       // decay mask of this wave's score tiles
-    if (!STATE_ONLY) {
+    {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
             const int q = 32 * mt + l32;
@@ -189,8 +180,8 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
     // ---- running state: St[i][j], j in this wave's slice ----------------------
     f32x16_t st[MT_D];
     // entering state: the scanned segment states, or (one segment) the caller's carried state
-    if (!STATE_ONLY && !REV && a.S == 1 && a.st_in) gSt = const_cast<float *>(a.st_in) + (size_t)scan * (D * D);
-    const bool has_init = !STATE_ONLY && gSt != nullptr && (a.S > 1 || (!REV && a.st_in));
+    if (!REV && a.S == 1 && a.st_in) gSt = const_cast<float *>(a.st_in) + (size_t)scan * (D * D);
+    const bool has_init = gSt != nullptr && (a.S > 1 || (!REV && a.st_in));
     if (has_init && a.transpose_init) {
         // The stored state is that of the scan with Bm and C exchanged: copy it to LDS
         // with coalesced 16-byte loads (the tiles' storage is still unused) and read it
@@ -234,7 +225,7 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
             const size_t off = (size_t)min(t, seg_hi - 1) * D + 8 * sc;
             rb[i] = *(const U4 *)(gB + off);
             rc[i] = *(const U4 *)(gC + off);
-            if (!STATE_ONLY) ra[i] = *(const U4 *)(gA + off);
+            ra[i] = *(const U4 *)(gA + off);
         }
     };
     // ---- registers -> LDS, transposing C and the weighted Bm ---------------------
@@ -246,10 +237,10 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
                 const U4 z = {0u, 0u, 0u, 0u};
                 rb[i] = ok ? rb[i] : z;
                 rc[i] = ok ? rc[i] : z;
-                if (!STATE_ONLY) ra[i] = ok ? ra[i] : z;
+                ra[i] = ok ? ra[i] : z;
             }
         }
-        if (!STATE_ONLY) {
+        {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 uint16_t *pa = sA + (4 * sa + i) * LDN + nat_off;
@@ -285,25 +276,14 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         }
     };
 
-    // Pre-pass only: the local state of a segment weights row r by lambda^(distance to
-    // the segment's far end).  Blocks whose largest weight is below 2^-skip_bits add
-    // less than fp32 rounding to a state whose nearest rows have weight 1, so they are
-    // not read at all: with decay, far context is numerically irrelevant.
-    int ib0 = 0;
-    if (STATE_ONLY && a.skip_bits > 0.f && lg < 0.f) {
-        const float reach = a.skip_bits / -lg;          // rows that still matter
-        if (reach < (float)(nblk * BK)) ib0 = max(0, nblk - ((int)(reach / BK) + 2));
-    }
+    load_block(rev ? nblk - 1 : 0);
 
-    load_block(rev ? nblk - 1 - ib0 : ib0);
-
-    for (int ib = ib0; ib < nblk; ++ib) {
+    for (int ib = 0; ib < nblk; ++ib) {
         const int blk = rev ? (nblk - 1 - ib) : ib;
         const int t0 = seg_lo + blk * BK;
         // the swizzle terms are re-derived per block (one XOR each) instead of living
         // in a register per address for the whole loop
         asm volatile("" : "+v"(tw_u), "+v"(tr_pg));
-        if (STATE_ONLY) __syncthreads();        // previous block's readers of sBT / sCT are done
         if (want_final && t0 + BK > seg_hi) {
             // The state handed back must be the one after the last real token: in the
             // final, partial block of m rows weight row r by lambda^(m-1-r) and decay the
@@ -323,14 +303,13 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
             for (int ks = 0; ks < KS_B; ++ks)
                 cf[ks] = *(const U4 *)(sCT + 32 * w * BK + tr_row + (tr_pg ^ (16 * (ks ^ (w & 3)))));
         };
-        if (STATE_ONLY) load_cf();
 
         // Operand fragments are read from LDS in batches of eight 16-byte loads that
         // are all issued before the MFMAs that consume them (a scheduling barrier keeps
         // the compiler from sinking each load next to its use): the LDS latency is paid
         // once per batch instead of once per MFMA.
         f32x16_t acc[2];
-        if (!STATE_ONLY) {
+        {
             // ---- scores: S^T tile (kt, qt) = Bm[kt] A[qt]^T, masked, to LDS as P[q][key]
 #pragma unroll
             for (int ti = 0; ti < NTILE; ++ti) {
@@ -448,7 +427,7 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
             st[mt] = s;
         }
 
-        if (!STATE_ONLY) {
+        {
             __syncthreads();                    // sO complete; every LDS tile of this block is dead
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -461,8 +440,8 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         }
     }
 
-    if (STATE_ONLY || want_final) {
-        float *dst = STATE_ONLY ? gSt : a.st_out + (size_t)scan * (D * D);
+    if (want_final) {
+        float *dst = a.st_out + (size_t)scan * (D * D);
 #pragma unroll
         for (int mt = 0; mt < MT_D; ++mt)
 #pragma unroll
