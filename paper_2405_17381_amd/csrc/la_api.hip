@@ -229,7 +229,7 @@ template <bool REV>
 int run_segment_scan(const ScanArgs &a, const LaLambdas &lams, long scans, int d, hipStream_t s)
 {
     SegScanArgs sa;
-    sa.states = a.states; sa.init = REV ? nullptr : a.st_in;
+    sa.states = a.states; sa.init = REV ? nullptr : a.st_in; sa.skip_bits = a.skip_bits;
     sa.H = a.H; sa.S = a.S; sa.L = a.L; sa.DD = d * d;
     dim3 grid((unsigned)((d * d / 4 + 255) / 256), (unsigned)scans), block(256);
     hipLaunchKernelGGL(la_segment_scan<REV>, grid, block, 0, s, sa, lams);

@@ -132,7 +132,6 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
     const uint16_t *gB = (const uint16_t *)a.Bm + base;
     const uint16_t *gC = (const uint16_t *)a.C + base;
     uint16_t *gO = (uint16_t *)a.Out + base;
-    float *gSt = a.states ? a.states + ((size_t)scan * a.S + seg) * (size_t)(D * D) : nullptr;
 
     // ---- per-lane constants --------------------------------------------------
     float wst[4];                              // state-update weight of staged rows
@@ -179,9 +178,9 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
 
     // ---- running state: St[i][j], j in this wave's slice ----------------------
     f32x16_t st[MT_D];
-    // entering state: the scanned segment states, or (one segment) the caller's carried state
-    if (!REV && a.S == 1 && a.st_in) gSt = const_cast<float *>(a.st_in) + (size_t)scan * (D * D);
-    const bool has_init = gSt != nullptr && (a.S > 1 || (!REV && a.st_in));
+    // entering state: a segment state, or (first segment) the caller's carried state, or zero
+    const float *gSt = la_entering_state(a, scan, seg, REV, lg, D * D);
+    const bool has_init = gSt != nullptr;
     if (has_init && a.transpose_init) {
         // The stored state is that of the scan with Bm and C exchanged: copy it to LDS
         // with coalesced 16-byte loads (the tiles' storage is still unused) and read it

@@ -62,12 +62,12 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
     // lambda^k, k = 0..BK, evaluated in double then rounded once
     for (int k = tid; k <= BK; k += 256) sPw[k] = (float)pow((double)lam, (double)k);
     // initial state
-    if (!STATE_ONLY && !REV && a.S == 1 && a.st_in) gSt = const_cast<float *>(a.st_in) + (size_t)scan * (D * D);
-    const bool has_init = !STATE_ONLY && gSt != nullptr && (a.S > 1 || (!REV && a.st_in));
+    const float *gIn = STATE_ONLY ? nullptr : la_entering_state(a, scan, seg, REV, lams.lg2[scan % a.H], D * D);
+    const bool has_init = gIn != nullptr;
     const bool want_final = !STATE_ONLY && !REV && a.st_out != nullptr && seg == a.S - 1;
     for (int e = tid; e < D * D; e += 256) {
         int i = e / D, j = e % D;
-        sKV[i * LD + j] = has_init ? (a.transpose_init ? gSt[j * D + i] : gSt[e]) : 0.0f;
+        sKV[i * LD + j] = has_init ? (a.transpose_init ? gIn[j * D + i] : gIn[e]) : 0.0f;
     }
     __syncthreads();
     float lamBK = sPw[BK];

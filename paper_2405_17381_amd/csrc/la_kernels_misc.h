@@ -16,6 +16,8 @@ __global__ __launch_bounds__(256) void la_segment_scan(SegScanArgs a, LaLambdas 
     const int e = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (e >= a.DD) return;
     const float lam = lams.v[scan % a.H];
+    // chain-free heads (see la_entering_state) read their neighbour's local state directly
+    if (a.skip_bits > 0.f && -lams.lg2[scan % a.H] * (float)a.L >= a.skip_bits) return;
     const float lamL = (float)pow((double)lam, (double)a.L);
     float *W = a.states + (size_t)scan * a.S * a.DD + e;
     float4 carry = make_float4(0.f, 0.f, 0.f, 0.f);
