@@ -92,3 +92,26 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(1, 1, 8, 64)
     with pytest.raises(ValueError):
         binding.la_fwd(x, x, x, [0.5])
+
+
+def test_inference_and_output_stage_entry_points_reject_bad_arguments():
+    """la_fwd_state, la_decode_step, la_gate_norm_*: every rejection precedes any HIP call."""
+    lib = binding.load_library()
+    lam = (ctypes.c_float * 1)(0.5)
+    P = 4096
+    # la_fwd_state: misaligned state pointers, bad shape
+    assert lib.la_fwd_state(P, P, P, lam, P, P + 4, 0, 1, 1, 8, 64, 1, 0, 0, None) == -7
+    assert lib.la_fwd_state(P, P, P, lam, P, 0, P + 8, 1, 1, 8, 64, 1, 0, 0, None) == -7
+    assert lib.la_fwd_state(P, P, P, lam, P, 0, 0, 1, 1, 8, 32, 1, 0, 0, None) == -2
+    # la_decode_step: missing state, bad lambda, bad dtype
+    assert lib.la_decode_step(P, P, P, lam, 0, P, 1, 1, 64, 1, None) == -1
+    bad = (ctypes.c_float * 1)(2.0)
+    assert lib.la_decode_step(P, P, P, bad, P, P, 1, 1, 64, 1, None) == -4
+    assert lib.la_decode_step(P, P, P, lam, P, P, 1, 1, 64, 5, None) == -3
+    # gate / norm stage: null, negative or non-finite eps, batch beyond the grid limit
+    assert lib.la_gate_norm_fwd(P, 0, P, 0.0, 1, 1, 8, 64, 1, None) == -1
+    assert lib.la_gate_norm_fwd(P, P, P, -1.0, 1, 1, 8, 64, 1, None) == -4
+    assert lib.la_gate_norm_fwd(P, P, P, float("nan"), 1, 1, 8, 64, 1, None) == -4
+    assert lib.la_gate_norm_fwd(P, P, P, 0.0, 70000, 1, 8, 64, 1, None) == -2
+    assert lib.la_gate_norm_bwd(P, P, P, P, 0, 0.0, 1, 1, 8, 64, 1, None) == -1
+    assert lib.la_gate_norm_bwd(P, P, P, P + 2, P, 0.0, 1, 1, 8, 64, 1, None) == -7
