@@ -196,7 +196,7 @@ hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
 }
 
 ScanArgs make_args(const void *A, const void *Bm, const void *C, void *Out, const Plan &p,
-                   int H, int n, float *states, int transpose_init)
+                   int H, int n, la_dtype dt, float *states, int transpose_init)
 {
     ScanArgs a;
     a.A = A; a.Bm = Bm; a.C = C; a.Out = Out;
@@ -204,9 +204,11 @@ ScanArgs make_args(const void *A, const void *Bm, const void *C, void *Out, cons
     a.n = n; a.H = H; a.L = p.L; a.S = p.S;
     a.B = 0;             // set by the callers that launch a pre-pass
     a.transpose_init = transpose_init;
-    // Pre-pass cut-off: 2^-48 of the nearest row's weight, far below the 2^-24
-    // resolution of the fp32 state it is added to (LA_NO_DECAY_SKIP reads everything).
-    a.skip_bits = std::getenv("LA_NO_DECAY_SKIP") ? 0.0f : 48.0f;
+    // Decay cut-off: contributions weighted below 2^-bits of the nearest row's weight are
+    // not read.  fp32: 2^-48, far below the 2^-24 resolution of the state they would be
+    // added to; bf16: 2^-32, far below both that and the 2^-8 resolution of the bf16
+    // operand the state is rounded to when it is used (LA_NO_DECAY_SKIP reads everything).
+    a.skip_bits = std::getenv("LA_NO_DECAY_SKIP") ? 0.0f : (dt == LA_BF16 ? 32.0f : 48.0f);
     a.rev = 0;
     a.st_in = nullptr;
     a.st_out = nullptr;
@@ -252,7 +254,7 @@ int run_scan(const void *A, const void *Bm, const void *C, void *Out, const LaLa
              const float *st_in = nullptr, float *st_out = nullptr)
 {
     const long scans = (long)B * H;
-    ScanArgs a = make_args(A, Bm, C, Out, p, H, n, states, 0);
+    ScanArgs a = make_args(A, Bm, C, Out, p, H, n, dt, states, 0);
     a.B = B;
     a.rev = REV ? 1 : 0;
     a.st_in = st_in;
@@ -299,11 +301,11 @@ int run_backward(const void *Q, const void *K, const void *V, const void *dO, vo
     float *ws_f = ws;
     float *ws_r = ws ? ws + (size_t)scans * p.S * (size_t)d * d : nullptr;
     ScanArgs pre[2];
-    pre[0] = make_args(dO, V, K, dQ, p, H, n, ws_f, 0);
-    pre[1] = make_args(V, dO, Q, dK, p, H, n, ws_r, 0);
+    pre[0] = make_args(dO, V, K, dQ, p, H, n, dt, ws_f, 0);
+    pre[1] = make_args(V, dO, Q, dK, p, H, n, dt, ws_r, 0);
     pre[1].rev = 1;
     pre[0].B = pre[1].B = B;
-    ScanArgs av = make_args(K, Q, dO, dV, p, H, n, ws_r, 1);
+    ScanArgs av = make_args(K, Q, dO, dV, p, H, n, dt, ws_r, 1);
     av.rev = 1;
     if (p.S > 1) {
         int rc = run_prepass(pre, 2, lams, scans, d, dt, s);

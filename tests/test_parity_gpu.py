@@ -135,8 +135,9 @@ def test_result_independent_of_segmentation_bf16():
 
 def test_decay_cutoff_of_the_prepass_is_invisible():
     """The segment-state pre-pass does not read rows whose decay weight is below
-    2^-48; against reading everything the outputs may differ by fp32 rounding of
-    the state at most."""
+    2^-32 (bf16) or 2^-48 (fp32); against reading everything the fp32 state moves
+    by far less than its own rounding, so outputs may differ only where that
+    flips the rounding of a bf16 operand or output (2^-8 of one value)."""
     lam = [0.5, 0.9, 0.95, 0.98, 0.9999, 1.0]
     w = synth.custom(1, len(lam), 8192, 128, lam, seed=99, dtype="bf16")
     xs = synth.draw(w)
@@ -147,7 +148,8 @@ def test_decay_cutoff_of_the_prepass_is_invisible():
     finally:
         os.environ.pop("LA_NO_DECAY_SKIP", None)
     for a, b in zip(cut, full):
-        assert oracle.rel_max_err(a, b) <= 1e-5
+        assert oracle.rel_max_err(a, b) <= 1e-3
+        assert np.mean(a != b) <= 1e-3          # flips are rare
     q, k, v, g = _ref_inputs(xs, "bf16")
     ref = (oracle.c_recurrence_fwd(q, k, v, lam),) + oracle.c_recurrence_bwd(q, k, v, lam, g)
     _compare(w, cut, ref, TOL["bf16"], "decay cut-off, n=8192, L=2048")
