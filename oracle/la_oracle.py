@@ -180,3 +180,34 @@ def gate_norm_bwd(O, U, dY, eps=0.0):
     c = np.mean(dN * O, axis=(1, 3), keepdims=True)
     dO = dN / r - O * c / (r ** 3)
     return dO, dU
+
+
+# --------------------------------------------------------------------------
+# activation of the query / key projections (Sec. 4.2, "Gating Mechanism":
+# Q = phi(X W_q), K = phi(X W_k), phi = Swish).  Reading: Swish with beta = 1,
+# phi(x) = x * sigmoid(x); the paper names the function and gives no beta.
+# --------------------------------------------------------------------------
+def swish(x):
+    """phi(x) = x / (1 + exp(-x)), fp64."""
+    x = _as64(x)
+    return x / (1.0 + np.exp(-x))
+
+
+def swish_grad(x):
+    """phi'(x) = s + x s (1 - s), s = sigmoid(x)."""
+    x = _as64(x)
+    s = 1.0 / (1.0 + np.exp(-x))
+    return s + x * s * (1.0 - s)
+
+
+def swish_attention_fwd(Qp, Kp, V, lam):
+    """O = attention(phi(Qp), phi(Kp), V): the attention of this file applied
+    to the activated projections."""
+    return recurrence_fwd(swish(Qp), swish(Kp), V, lam)
+
+
+def swish_attention_bwd(Qp, Kp, V, lam, dO):
+    """Gradients with respect to the pre-activations: chain rule through phi,
+    dQp = dQ * phi'(Qp), dKp = dK * phi'(Kp); dV is the attention's own."""
+    dQ, dK, dV = recurrence_bwd(swish(Qp), swish(Kp), V, lam, dO)
+    return dQ * swish_grad(Qp), dK * swish_grad(Kp), dV

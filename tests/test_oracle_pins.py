@@ -6,6 +6,8 @@ the two independent forms (App. A proves them equal), finite differences,
 a blocked re-statement of Alg. 5/6 (App. C proves block form == token form),
 the trilinearity invariant and causality.
 """
+import math
+
 import numpy as np
 import pytest
 
@@ -329,3 +331,59 @@ def test_gate_norm_gradients_by_finite_differences(eps):
     if eps == 0.0:
         # the normalised output does not change along O: <dO, O> = 0 per token
         np.testing.assert_allclose(np.sum(dO * O, axis=(1, 3)), 0.0, atol=1e-12)
+
+
+# ---- 12. Swish on the query / key projections (Sec. 4.2) ------------------------------
+def test_swish_known_values_and_identities():
+    # phi(0) = 0, phi'(0) = 1/2, phi(1) = 1 / (1 + 1/e), phi(-1) = -1 / (1 + e)
+    assert oracle.swish(0.0) == 0.0
+    assert oracle.swish_grad(0.0) == 0.5
+    assert abs(oracle.swish(1.0) - 1.0 / (1.0 + math.exp(-1.0))) < 1e-16
+    assert abs(oracle.swish(-1.0) + 1.0 / (1.0 + math.e)) < 1e-16
+    # sigmoid(x) + sigmoid(-x) = 1  =>  phi(x) - phi(-x) = x  and  phi'(x) + phi'(-x) = 1
+    x = np.linspace(-12.0, 12.0, 97)
+    np.testing.assert_allclose(oracle.swish(x) - oracle.swish(-x), x, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(oracle.swish_grad(x) + oracle.swish_grad(-x), 1.0, rtol=0, atol=1e-14)
+    # large |x|: phi -> x (right), -> 0 (left)
+    assert abs(oracle.swish(40.0) - 40.0) < 1e-15 and abs(oracle.swish(-40.0)) < 1e-15
+    # the single minimum: phi'(x*) = 0 gives x* sigma(x*) = 1 + x*, i.e. phi(x*) = 1 + x*;
+    # found here by bisection on phi' alone
+    lo, hi = -2.0, -1.0
+    for _ in range(80):
+        mid = 0.5 * (lo + hi)
+        if oracle.swish_grad(mid) < 0.0:
+            lo = mid
+        else:
+            hi = mid
+    xs = 0.5 * (lo + hi)
+    assert abs(xs + 1.2784645427610738) < 1e-12
+    assert abs(oracle.swish(xs) - (1.0 + xs)) < 1e-12
+    assert np.all(oracle.swish(x) >= oracle.swish(xs) - 1e-15)
+    # derivative by central differences
+    h = 1e-6
+    fd = (oracle.swish(x + h) - oracle.swish(x - h)) / (2 * h)
+    np.testing.assert_allclose(oracle.swish_grad(x), fd, rtol=0, atol=1e-8)
+
+
+def test_swish_attention_gradients_by_finite_differences():
+    """The composed loss <dO, attention(phi(Qp), phi(Kp), V)> differentiated
+    numerically with respect to the pre-activations."""
+    rng = np.random.default_rng(12)
+    shape = (1, 2, 5, 3)
+    lam = [0.8, 1.0]
+    Qp, Kp, V, dO = (rng.standard_normal(shape) for _ in range(4))
+    dQp, dKp, dV = oracle.swish_attention_bwd(Qp, Kp, V, lam, dO)
+    loss = lambda q, k, v: float(np.sum(dO * oracle.left_product_fwd(oracle.swish(q), oracle.swish(k), v, lam)))
+    h = 1e-6
+    for which, grad in ((0, dQp), (1, dKp), (2, dV)):
+        for idx in np.ndindex(shape):
+            a = [Qp.copy(), Kp.copy(), V.copy()]
+            b = [Qp.copy(), Kp.copy(), V.copy()]
+            a[which][idx] += h
+            b[which][idx] -= h
+            fd = (loss(*a) - loss(*b)) / (2 * h)
+            assert abs(fd - grad[idx]) <= 2e-8 * max(1.0, abs(grad[idx])), (which, idx)
+    # forward: the activation is applied to Q and K only, never to V
+    O = oracle.swish_attention_fwd(Qp, Kp, V, lam)
+    np.testing.assert_allclose(O, oracle.left_product_fwd(oracle.swish(Qp), oracle.swish(Kp), V, lam), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(oracle.swish_attention_fwd(Qp, Kp, 2.0 * V, lam), 2.0 * O, rtol=1e-12)
