@@ -153,6 +153,31 @@ int la_gate_norm_fwd(const void *O, const void *U, void *Y, float eps,
 int la_gate_norm_bwd(const void *O, const void *U, const void *dY, void *dO, void *dU, float eps,
                      int B, int H, int n, int d, la_dtype dt, void *hip_stream);
 
+/*
+ * Forward and backward with the activation of the query / key projections
+ * fused in (Sec. 4.2, "Gating Mechanism": Q = phi(X W_q), K = phi(X W_k), phi =
+ * Swish, read as phi(x) = x * sigmoid(x)).  Qp, Kp are the pre-activations:
+ *     la_fwd_swish:  O = lightning_attention(phi(Qp), phi(Kp), V, lambda)
+ *     la_bwd_swish:  with (dQ, dK, dV) the gradients la_bwd gives for Q = phi(Qp),
+ *                    K = phi(Kp):  dQp = dQ * phi'(Qp),  dKp = dK * phi'(Kp),  dV.
+ * phi is evaluated in fp32 while a tile is staged and rounded to dt before the
+ * contractions (what they would see had phi(Qp), phi(Kp) been stored); phi',
+ * in fp32, multiplies the result tile as it is stored.  Neither activated
+ * tensor ever exists in memory.  Arguments, workspace and errors as la_fwd / la_bwd.
+ */
+int la_fwd_swish(const void *Qp, const void *Kp, const void *V,
+                 const float *lambda /* host, [H] */,
+                 void *O,
+                 int B, int H, int n, int d, la_dtype dt,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+int la_bwd_swish(const void *Qp, const void *Kp, const void *V,
+                 const float *lambda /* host, [H] */,
+                 const void *dO,
+                 void *dQp, void *dKp, void *dV,
+                 int B, int H, int n, int d, la_dtype dt,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static, human-readable text for an la_status value. */
 const char *la_strerror(int status);
 

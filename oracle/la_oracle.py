@@ -190,13 +190,15 @@ def gate_norm_bwd(O, U, dY, eps=0.0):
 def swish(x):
     """phi(x) = x / (1 + exp(-x)), fp64."""
     x = _as64(x)
-    return x / (1.0 + np.exp(-x))
+    with np.errstate(over="ignore"):        # exp(-x) = inf for x << 0 gives the limit 0
+        return x / (1.0 + np.exp(-x))
 
 
 def swish_grad(x):
     """phi'(x) = s + x s (1 - s), s = sigmoid(x)."""
     x = _as64(x)
-    s = 1.0 / (1.0 + np.exp(-x))
+    with np.errstate(over="ignore"):
+        s = 1.0 / (1.0 + np.exp(-x))
     return s + x * s * (1.0 - s)
 
 

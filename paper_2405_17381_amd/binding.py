@@ -15,7 +15,8 @@ import torch
 LA_F32, LA_BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libla.so")
-EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_fwd_state", "la_decode_step", "la_gate_norm_fwd", "la_gate_norm_bwd", "la_strerror", "la_plan",
+EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_fwd_state", "la_decode_step", "la_gate_norm_fwd",
+           "la_gate_norm_bwd", "la_fwd_swish", "la_bwd_swish", "la_strerror", "la_plan",
            "la_profile_enable", "la_profile_collect")
 _lib = None
 
@@ -42,6 +43,10 @@ def load_library():
     lib.la_fwd.restype = ci
     lib.la_bwd.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.la_bwd.restype = ci
+    lib.la_fwd_swish.argtypes = lib.la_fwd.argtypes
+    lib.la_fwd_swish.restype = ci
+    lib.la_bwd_swish.argtypes = lib.la_bwd.argtypes
+    lib.la_bwd_swish.restype = ci
     lib.la_fwd_state.argtypes = [vp, vp, vp, fp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.la_fwd_state.restype = ci
     lib.la_decode_step.argtypes = [vp, vp, vp, fp, vp, vp, ci, ci, ci, ci, vp]
@@ -118,7 +123,7 @@ def _workspace(B, H, n, d, dt, is_bwd, device, workspace: Optional[torch.Tensor]
     return workspace, workspace.data_ptr(), workspace.numel() * workspace.element_size()
 
 
-def la_fwd(Q, K, V, lam, O=None, workspace: Optional[torch.Tensor] = None):
+def la_fwd(Q, K, V, lam, O=None, workspace: Optional[torch.Tensor] = None, _entry: str = "la_fwd"):
     """O = la_fwd(Q, K, V, lambda) on the current CUDA(HIP) stream."""
     _check([Q, K, V])
     B, H, n, d = Q.shape
@@ -130,11 +135,16 @@ def la_fwd(Q, K, V, lam, O=None, workspace: Optional[torch.Tensor] = None):
     ws, ws_ptr, ws_bytes = _workspace(B, H, n, d, dt, False, Q.device, workspace)
     with torch.cuda.device(Q.device):
         stream = torch.cuda.current_stream().cuda_stream
-        rc = load_library().la_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _lam(lam, H),
-                                   O.data_ptr(), B, H, n, d, dt, ws_ptr, ws_bytes, stream)
+        rc = getattr(load_library(), _entry)(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _lam(lam, H),
+                                             O.data_ptr(), B, H, n, d, dt, ws_ptr, ws_bytes, stream)
     if rc != 0:
-        raise LaError(rc, "la_fwd")
+        raise LaError(rc, _entry)
     return O
+
+
+def la_fwd_swish(Qp, Kp, V, lam, O=None, workspace: Optional[torch.Tensor] = None):
+    """O = la_fwd(swish(Qp), swish(Kp), V, lambda), the activation applied inside the kernels."""
+    return la_fwd(Qp, Kp, V, lam, O=O, workspace=workspace, _entry="la_fwd_swish")
 
 
 def _check_state(kv, B, H, d, device):
@@ -188,7 +198,8 @@ def la_decode_step(q, k, v, lam, kv, o=None):
     return o
 
 
-def la_bwd(Q, K, V, lam, dO, dQ=None, dK=None, dV=None, workspace: Optional[torch.Tensor] = None):
+def la_bwd(Q, K, V, lam, dO, dQ=None, dK=None, dV=None, workspace: Optional[torch.Tensor] = None,
+           _entry: str = "la_bwd"):
     """(dQ, dK, dV) = la_bwd(Q, K, V, lambda, dO) on the current stream."""
     _check([Q, K, V, dO])
     B, H, n, d = Q.shape
@@ -200,12 +211,17 @@ def la_bwd(Q, K, V, lam, dO, dQ=None, dK=None, dV=None, workspace: Optional[torc
     ws, ws_ptr, ws_bytes = _workspace(B, H, n, d, dt, True, Q.device, workspace)
     with torch.cuda.device(Q.device):
         stream = torch.cuda.current_stream().cuda_stream
-        rc = load_library().la_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _lam(lam, H),
-                                   dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
-                                   B, H, n, d, dt, ws_ptr, ws_bytes, stream)
+        rc = getattr(load_library(), _entry)(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _lam(lam, H),
+                                             dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                                             B, H, n, d, dt, ws_ptr, ws_bytes, stream)
     if rc != 0:
-        raise LaError(rc, "la_bwd")
+        raise LaError(rc, _entry)
     return dQ, dK, dV
+
+
+def la_bwd_swish(Qp, Kp, V, lam, dO, dQp=None, dKp=None, dV=None, workspace: Optional[torch.Tensor] = None):
+    """Gradients of la_fwd_swish with respect to the pre-activations Qp, Kp and to V."""
+    return la_bwd(Qp, Kp, V, lam, dO, dQ=dQp, dK=dKp, dV=dV, workspace=workspace, _entry="la_bwd_swish")
 
 
 def la_gate_norm_fwd(O, U, eps: float = 0.0, Y=None):

@@ -138,11 +138,11 @@ hipError_t allow_lds(K kernel, size_t bytes)
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-template <int D, bool REV>
+template <int D, bool REV, bool ACT>
 hipError_t launch_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
     using Cfg = Bf16Cfg<D>;
-    auto kern = la_scan_bf16<D, REV>;
+    auto kern = la_scan_bf16<D, REV, ACT>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
@@ -154,11 +154,11 @@ hipError_t launch_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s
     return hipGetLastError();
 }
 
-template <int D>
+template <int D, bool ACT>
 hipError_t launch_prepass_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
     using Cfg = PrepassCfg<D>;
-    auto kern = la_prepass_bf16<D>;
+    auto kern = la_prepass_bf16<D, ACT>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
@@ -187,9 +187,14 @@ hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
                               la_dtype dt, hipStream_t s)
 {
     if (dt == LA_BF16) {
-        if (STATE_ONLY) return d == 64 ? launch_prepass_bf16<64>(a, lams, s) : launch_prepass_bf16<128>(a, lams, s);
-        if (d == 64) return launch_bf16<64, REV>(a, lams, s);
-        return launch_bf16<128, REV>(a, lams, s);
+        // the plain path runs kernels without any activation code in them
+        const bool act = (a.r[0].act | a.r[a.nroles - 1].act) != 0;
+        if (STATE_ONLY) {
+            if (act) return d == 64 ? launch_prepass_bf16<64, true>(a, lams, s) : launch_prepass_bf16<128, true>(a, lams, s);
+            return d == 64 ? launch_prepass_bf16<64, false>(a, lams, s) : launch_prepass_bf16<128, false>(a, lams, s);
+        }
+        if (act) return d == 64 ? launch_bf16<64, REV, true>(a, lams, s) : launch_bf16<128, REV, true>(a, lams, s);
+        return d == 64 ? launch_bf16<64, REV, false>(a, lams, s) : launch_bf16<128, REV, false>(a, lams, s);
     }
     if (d == 64) return launch_f32<64, 64, REV, STATE_ONLY>(a, lams, s);
     return launch_f32<128, 32, REV, STATE_ONLY>(a, lams, s);
@@ -212,6 +217,8 @@ ScanArgs make_args(const void *A, const void *Bm, const void *C, void *Out, cons
     a.rev = 0;
     a.st_in = nullptr;
     a.st_out = nullptr;
+    a.act = 0;
+    a.E = nullptr;
     return a;
 }
 
@@ -251,10 +258,11 @@ int run_block_scan(const ScanArgs &a, const LaLambdas &lams, long scans, int d, 
 template <bool REV>
 int run_scan(const void *A, const void *Bm, const void *C, void *Out, const LaLambdas &lams,
              const Plan &p, int B, int H, int n, int d, la_dtype dt, float *states, hipStream_t s,
-             const float *st_in = nullptr, float *st_out = nullptr)
+             const float *st_in = nullptr, float *st_out = nullptr, int act = 0)
 {
     const long scans = (long)B * H;
     ScanArgs a = make_args(A, Bm, C, Out, p, H, n, dt, states, 0);
+    a.act = act;
     a.B = B;
     a.rev = REV ? 1 : 0;
     a.st_in = st_in;
@@ -293,9 +301,11 @@ int run_reverse_pair(const ScanArgs &ak, const ScanArgs &av, const LaLambdas &la
 // second loop is the reverse pair above.  With segments, the two pre-passes (forward
 // states of (V, K), reverse states of (dO, Q)) run as one launch into the two halves
 // of the scratch, then the two segment scans, then the block scans.
+// With `swish`, Q and K are pre-activations: they are activated wherever they are an
+// operand, and dQ, dK are multiplied by phi'(Q), phi'(K) as they are stored.
 int run_backward(const void *Q, const void *K, const void *V, const void *dO, void *dQ, void *dK,
                  void *dV, const LaLambdas &lams, const Plan &p, int B, int H, int n, int d,
-                 la_dtype dt, float *ws, hipStream_t s)
+                 la_dtype dt, float *ws, hipStream_t s, bool swish)
 {
     const long scans = (long)B * H;
     float *ws_f = ws;
@@ -307,6 +317,11 @@ int run_backward(const void *Q, const void *K, const void *V, const void *dO, vo
     pre[0].B = pre[1].B = B;
     ScanArgs av = make_args(K, Q, dO, dV, p, H, n, dt, ws_r, 1);
     av.rev = 1;
+    if (swish) {
+        pre[0].act = LA_ACT_C | LA_ACT_OUT; pre[0].E = Q;      // dQ = scan(dO, V, phi(K)) * phi'(Q)
+        pre[1].act = LA_ACT_C | LA_ACT_OUT; pre[1].E = K;      // dK = scan_rev(V, dO, phi(Q)) * phi'(K)
+        av.act = LA_ACT_A | LA_ACT_BM;                         // dV = scan_rev(phi(K), phi(Q), dO)
+    }
     if (p.S > 1) {
         int rc = run_prepass(pre, 2, lams, scans, d, dt, s);
         if (rc == LA_OK) rc = run_segment_scan<false>(pre[0], lams, scans, d, s);
@@ -342,6 +357,47 @@ int run_gate_norm(const GateArgs &g, int B, int n, int d, la_dtype dt, hipStream
     return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 
+// Argument checks and planning shared by the forward entry points.
+int forward(const void *Q, const void *K, const void *V, const float *lambda, void *O,
+            const float *kv_in, float *kv_out, int B, int H, int n, int d, la_dtype dt,
+            void *workspace, size_t workspace_bytes, void *hip_stream, int act)
+{
+    int rc = check_common(B, H, n, d, dt);
+    if (rc != LA_OK) return rc;
+    if (!Q || !K || !V || !O || !lambda) return LA_ERR_NULL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) ||
+        !aligned16(kv_in) || !aligned16(kv_out)) return LA_ERR_ALIGN;
+    LaLambdas lams;
+    rc = check_lambda(lambda, H, &lams);
+    if (rc != LA_OK) return rc;
+    const Plan p = make_plan(B, H, n, d, dt);
+    rc = check_workspace(p, B, H, d, workspace, workspace_bytes, false);
+    if (rc != LA_OK) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    // O = scan(Q, K, V)                                                   (Alg. 5)
+    return run_scan<false>(Q, K, V, O, lams, p, B, H, n, d, dt, (float *)workspace, s, kv_in, kv_out, act);
+}
+
+// ... and by the backward entry points.
+int backward(const void *Q, const void *K, const void *V, const float *lambda, const void *dO,
+             void *dQ, void *dK, void *dV, int B, int H, int n, int d, la_dtype dt,
+             void *workspace, size_t workspace_bytes, void *hip_stream, bool swish)
+{
+    int rc = check_common(B, H, n, d, dt);
+    if (rc != LA_OK) return rc;
+    if (!Q || !K || !V || !dO || !dQ || !dK || !dV || !lambda) return LA_ERR_NULL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(dO) ||
+        !aligned16(dQ) || !aligned16(dK) || !aligned16(dV)) return LA_ERR_ALIGN;
+    LaLambdas lams;
+    rc = check_lambda(lambda, H, &lams);
+    if (rc != LA_OK) return rc;
+    const Plan p = make_plan(B, H, n, d, dt);
+    rc = check_workspace(p, B, H, d, workspace, workspace_bytes, true);
+    if (rc != LA_OK) return rc;
+    return run_backward(Q, K, V, dO, dQ, dK, dV, lams, p, B, H, n, d, dt, (float *)workspace,
+                        (hipStream_t)hip_stream, swish);
+}
+
 }  // namespace
 
 extern "C" {
@@ -369,28 +425,25 @@ int la_fwd_state(const void *Q, const void *K, const void *V, const float *lambd
                  int B, int H, int n, int d, la_dtype dt,
                  void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    int rc = check_common(B, H, n, d, dt);
-    if (rc != LA_OK) return rc;
-    if (!Q || !K || !V || !O || !lambda) return LA_ERR_NULL;
-    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) ||
-        !aligned16(kv_in) || !aligned16(kv_out)) return LA_ERR_ALIGN;
-    LaLambdas lams;
-    rc = check_lambda(lambda, H, &lams);
-    if (rc != LA_OK) return rc;
-    const Plan p = make_plan(B, H, n, d, dt);
-    rc = check_workspace(p, B, H, d, workspace, workspace_bytes, false);
-    if (rc != LA_OK) return rc;
-    hipStream_t s = (hipStream_t)hip_stream;
-    // O = scan(Q, K, V)                                                   (Alg. 5)
-    return run_scan<false>(Q, K, V, O, lams, p, B, H, n, d, dt, (float *)workspace, s, kv_in, kv_out);
+    return forward(Q, K, V, lambda, O, kv_in, kv_out, B, H, n, d, dt, workspace, workspace_bytes,
+                   hip_stream, 0);
 }
 
 int la_fwd(const void *Q, const void *K, const void *V, const float *lambda, void *O,
            int B, int H, int n, int d, la_dtype dt,
            void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    return la_fwd_state(Q, K, V, lambda, O, nullptr, nullptr, B, H, n, d, dt,
-                        workspace, workspace_bytes, hip_stream);
+    return forward(Q, K, V, lambda, O, nullptr, nullptr, B, H, n, d, dt, workspace, workspace_bytes,
+                   hip_stream, 0);
+}
+
+int la_fwd_swish(const void *Qp, const void *Kp, const void *V, const float *lambda, void *O,
+                 int B, int H, int n, int d, la_dtype dt,
+                 void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    // O = scan(phi(Qp), phi(Kp), V)
+    return forward(Qp, Kp, V, lambda, O, nullptr, nullptr, B, H, n, d, dt, workspace, workspace_bytes,
+                   hip_stream, LA_ACT_A | LA_ACT_BM);
 }
 
 int la_decode_step(const void *q, const void *k, const void *v, const float *lambda,
@@ -421,19 +474,17 @@ int la_bwd(const void *Q, const void *K, const void *V, const float *lambda, con
            int B, int H, int n, int d, la_dtype dt,
            void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    int rc = check_common(B, H, n, d, dt);
-    if (rc != LA_OK) return rc;
-    if (!Q || !K || !V || !dO || !dQ || !dK || !dV || !lambda) return LA_ERR_NULL;
-    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(dO) ||
-        !aligned16(dQ) || !aligned16(dK) || !aligned16(dV)) return LA_ERR_ALIGN;
-    LaLambdas lams;
-    rc = check_lambda(lambda, H, &lams);
-    if (rc != LA_OK) return rc;
-    const Plan p = make_plan(B, H, n, d, dt);
-    rc = check_workspace(p, B, H, d, workspace, workspace_bytes, true);
-    if (rc != LA_OK) return rc;
-    return run_backward(Q, K, V, dO, dQ, dK, dV, lams, p, B, H, n, d, dt, (float *)workspace,
-                        (hipStream_t)hip_stream);
+    return backward(Q, K, V, lambda, dO, dQ, dK, dV, B, H, n, d, dt, workspace, workspace_bytes,
+                    hip_stream, false);
+}
+
+int la_bwd_swish(const void *Qp, const void *Kp, const void *V, const float *lambda, const void *dO,
+                 void *dQp, void *dKp, void *dV,
+                 int B, int H, int n, int d, la_dtype dt,
+                 void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return backward(Qp, Kp, V, lambda, dO, dQp, dKp, dV, B, H, n, d, dt, workspace, workspace_bytes,
+                    hip_stream, true);
 }
 
 int la_gate_norm_fwd(const void *O, const void *U, void *Y, float eps,

@@ -61,7 +61,29 @@ struct ScanArgs {
     const float *st_in;  // forward scans only: state carried in from earlier tokens,
                          // [scans, D, D] fp32 (rows = Bm feature), or nullptr for zero
     float *st_out;       // forward scans only: state after the last token, or nullptr
+    int act;             // LA_ACT_* bits: operands that are pre-activations (Swish is applied
+                         // as they are staged) and whether Out is a pre-activation gradient
+    const void *E;       // LA_ACT_OUT: the pre-activation whose gradient Out is, [scans, n, D]
 };
+
+// Swish on the query / key projections (Sec. 4.2: Q = phi(X W_q), K = phi(X W_k)).
+// The scans take the pre-activations and apply phi while staging a tile; a scan
+// whose result is the gradient of an activated operand multiplies it by phi' of the
+// matching pre-activation tile as it is stored (chain rule).
+enum : int { LA_ACT_A = 1, LA_ACT_BM = 2, LA_ACT_C = 4, LA_ACT_OUT = 8 };
+
+// phi(x) = x sigmoid(x).  exp2 overflows to +inf for x < -88, giving sigmoid = 0: the limit.
+__device__ __forceinline__ float la_sigmoid(float x)
+{
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+}
+__device__ __forceinline__ float la_swish(float x) { return x * la_sigmoid(x); }
+// phi'(x) = s (1 + x (1 - s)), s = sigmoid(x)
+__device__ __forceinline__ float la_swish_grad(float x)
+{
+    const float sg = la_sigmoid(x);
+    return sg * fmaf(x, 1.0f - sg, 1.0f);
+}
 
 // One launch of the block-scan kernel runs one scan, or two scans that read
 // mostly the same tensors (the dK and dV scans of Alg. 6's second loop).  In a

@@ -74,6 +74,26 @@ __device__ __forceinline__ f32x16_t mfma32(const U4 &a, const U4 &b, f32x16_t c)
 __device__ __forceinline__ int tt_row(int f) { return (f & ~9) | ((f & 1) << 3) | ((f >> 3) & 1); }
 __device__ __forceinline__ int tt_phi(int f) { return (f & 7) ^ ((f >> 4) & 7); }
 
+// Swish of the 8 bf16 values of a 16-byte chunk (fp32 inside, rounded back to bf16:
+// the contractions see what they would see had the activated tensor been stored).
+__device__ __forceinline__ U4 swish_u4(U4 r)
+{
+    U4 o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o[j] = pack2_bf16(la_swish(bf16_lo(r[j])), la_swish(bf16_hi(r[j])));
+    return o;
+}
+// 8 bf16 results times phi' of the 8 bf16 pre-activations in `x`
+__device__ __forceinline__ U4 mul_swish_grad_u4(U4 r, U4 x)
+{
+    U4 o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        o[j] = pack2_bf16(bf16_lo(r[j]) * la_swish_grad(bf16_lo(x[j])),
+                          bf16_hi(r[j]) * la_swish_grad(bf16_hi(x[j])));
+    return o;
+}
+
 template <int D>
 struct Bf16Cfg {
     static constexpr int BK = 64;
@@ -85,7 +105,8 @@ struct Bf16Cfg {
     static constexpr size_t lds_bytes = 2 * (size_t)(nA + nB + nBT + nCT + nP);
 };
 
-template <int D, bool REV>
+// ACT: the launch may carry LA_ACT_* flags (Swish prologue / epilogue).
+template <int D, bool REV, bool ACT>
 __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLambdas lams)
 {
     using Cfg = Bf16Cfg<D>;
@@ -132,6 +153,8 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
     const uint16_t *gB = (const uint16_t *)a.Bm + base;
     const uint16_t *gC = (const uint16_t *)a.C + base;
     uint16_t *gO = (uint16_t *)a.Out + base;
+    const int act = ACT ? a.act : 0;
+    const uint16_t *gE = (ACT && (act & LA_ACT_OUT)) ? (const uint16_t *)a.E + base : gA;
 
     // ---- per-lane constants --------------------------------------------------
     float wst[4];                              // state-update weight of staged rows
@@ -141,7 +164,8 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         wst[i] = rev ? pw(r) : pw(BK - 1 - r);
     }
     float lamBK = pw(BK);
-    const bool want_final = !REV && a.st_out != nullptr && seg == a.S - 1;
+    // (the activation variants have no entry point that hands a state back)
+    const bool want_final = !REV && !ACT && a.st_out != nullptr && seg == a.S - 1;
     // row-major tiles: this thread's two 8-byte pieces of chunk sc
     const int nat_off = 16 * (sc >> 1) + 4 * (sc & 1);
     // transposed tiles, stores: feature f = 8sc + e lives in physical row
@@ -237,6 +261,20 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
                 rb[i] = ok ? rb[i] : z;
                 rc[i] = ok ? rc[i] : z;
                 ra[i] = ok ? ra[i] : z;
+            }
+        }
+        if (ACT) {                              // phi(0) = 0: the zero padding stays zero
+            if (act & LA_ACT_A) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) ra[i] = swish_u4(ra[i]);
+            }
+            if (act & LA_ACT_BM) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) rb[i] = swish_u4(rb[i]);
+            }
+            if (act & LA_ACT_C) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) rc[i] = swish_u4(rc[i]);
             }
         }
         {
@@ -410,6 +448,14 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
                 }
         }
 
+        // Epilogue operand: the pre-activation tile whose phi' scales Out.  Loaded here, where
+        // the Out accumulators have just died, and used after the state update.
+        U4 re[4];
+        if (ACT && (act & LA_ACT_OUT)) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                re[i] = *(const U4 *)(gE + (size_t)min(t0 + 4 * sa + i, seg_hi - 1) * D + 8 * sc);
+        }
         // ---- state update: St = lambda^BK St + (w Bm)^T C ---------------------------
 #pragma unroll
         for (int mt = 0; mt < MT_D; ++mt) {
@@ -434,7 +480,9 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
                 const uint16_t *po = sO + (4 * sa + i) * LDN + nat_off;
                 U2 lo = *(const U2 *)(po);
                 U2 hi = *(const U2 *)(po + 8);
-                if (t < seg_hi) *(U4 *)(gO + (size_t)t * D + 8 * sc) = U4{lo[0], lo[1], hi[0], hi[1]};
+                U4 out = {lo[0], lo[1], hi[0], hi[1]};
+                if (ACT && (act & LA_ACT_OUT)) out = mul_swish_grad_u4(out, re[i]);
+                if (t < seg_hi) *(U4 *)(gO + (size_t)t * D + 8 * sc) = out;
             }
         }
     }

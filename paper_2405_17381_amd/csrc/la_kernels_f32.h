@@ -57,6 +57,7 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
     const float *gB = (const float *)a.Bm + (size_t)scan * a.n * D;
     const float *gC = (const float *)a.C + (size_t)scan * a.n * D;
     float *gO = (float *)a.Out + (size_t)scan * a.n * D;
+    const float *gE = (a.act & LA_ACT_OUT) ? (const float *)a.E + (size_t)scan * a.n * D : gA;
     float *gSt = a.states ? a.states + ((size_t)scan * a.S + seg) * (size_t)(D * D) : nullptr;
 
     // lambda^k, k = 0..BK, evaluated in double then rounded once
@@ -89,6 +90,11 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
                 vb = *(const float4 *)(gB + (size_t)t * D + c4);
                 vc = *(const float4 *)(gC + (size_t)t * D + c4);
                 if (!STATE_ONLY) va = *(const float4 *)(gA + (size_t)t * D + c4);
+                // Swish prologue on the operands that are pre-activations
+                if (a.act & LA_ACT_BM) vb = make_float4(la_swish(vb.x), la_swish(vb.y), la_swish(vb.z), la_swish(vb.w));
+                if (a.act & LA_ACT_C) vc = make_float4(la_swish(vc.x), la_swish(vc.y), la_swish(vc.z), la_swish(vc.w));
+                if (!STATE_ONLY && (a.act & LA_ACT_A))
+                    va = make_float4(la_swish(va.x), la_swish(va.y), la_swish(va.z), la_swish(va.w));
             }
             float *pb = sB + r * LD + c4, *pc = sC + r * LD + c4, *pa = sA + r * LD + c4;
             pb[0] = vb.x; pb[1] = vb.y; pb[2] = vb.z; pb[3] = vb.w;
@@ -163,7 +169,11 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
                 if (t < seg_hi) {
 #pragma unroll
                     for (int j = 0; j < CJ; ++j)
-                        gO[(size_t)t * D + tx + 16 * j] = fmaf(rs, ox[i][j], oi[i][j]);
+                    {
+                        float o = fmaf(rs, ox[i][j], oi[i][j]);
+                        if (a.act & LA_ACT_OUT) o *= la_swish_grad(gE[(size_t)t * D + tx + 16 * j]);
+                        gO[(size_t)t * D + tx + 16 * j] = o;
+                    }
                 }
             }
             __syncthreads();   // everyone is done reading the old state

@@ -25,7 +25,7 @@ struct PrepassCfg {
     static constexpr size_t lds_bytes = 2 * (size_t)(4 * nT);   // 2 buffers x (Bm^T, C^T)
 };
 
-template <int D>
+template <int D, bool ACT>
 __global__ __launch_bounds__(D * 2, 2) void la_prepass_bf16(ScanLaunch launch, LaLambdas lams)
 {
     using Cfg = PrepassCfg<D>;
@@ -113,6 +113,16 @@ __global__ __launch_bounds__(D * 2, 2) void la_prepass_bf16(ScanLaunch launch, L
                 const U4 z = {0u, 0u, 0u, 0u};
                 rb[i] = ok ? rb[i] : z;
                 rc[i] = ok ? rc[i] : z;
+            }
+        }
+        if (ACT) {                                           // Swish prologue, as the block scan's
+            if (a.act & LA_ACT_BM) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) rb[i] = swish_u4(rb[i]);
+            }
+            if (a.act & LA_ACT_C) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) rc[i] = swish_u4(rc[i]);
             }
         }
         const float w0 = wrow[0] * mu, w1 = wrow[1] * mu, w2 = wrow[2] * mu, w3 = wrow[3] * mu;

@@ -115,3 +115,7 @@ def test_inference_and_output_stage_entry_points_reject_bad_arguments():
     assert lib.la_gate_norm_fwd(P, P, P, 0.0, 70000, 1, 8, 64, 1, None) == -2
     assert lib.la_gate_norm_bwd(P, P, P, P, 0, 0.0, 1, 1, 8, 64, 1, None) == -1
     assert lib.la_gate_norm_bwd(P, P, P, P + 2, P, 0.0, 1, 1, 8, 64, 1, None) == -7
+    # fused-activation entry points share the checks of la_fwd / la_bwd
+    assert lib.la_fwd_swish(P, P, P, lam, 0, 1, 1, 8, 64, 1, 0, 0, None) == -1
+    assert lib.la_fwd_swish(P, P, P, lam, P, 1, 1, 8, 96, 1, 0, 0, None) == -2
+    assert lib.la_bwd_swish(P, P, P, lam, P, P, P + 4, P, 1, 1, 8, 64, 1, 0, 0, None) == -7

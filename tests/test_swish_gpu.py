@@ -1,0 +1,96 @@
+"""GPU parity of the attention with the Swish of the query / key projections fused
+in (la_fwd_swish, la_bwd_swish) against the CPU oracle."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2405_17381_amd import binding
+
+pytestmark = pytest.mark.gpu
+TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def _draw(B, H, n, d, dtype, seed):
+    """Pre-activations ~ N(0,1) (what a projection of normalised inputs gives), V scaled by
+    1/d so that outputs stay O(1); the oracle sees the values after the cast to `dtype`."""
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    Qp, Kp, V, dO = [torch.randn((B, H, n, d), generator=g) for _ in range(4)]
+    V = V / d
+    return [x.to(TDT[dtype]) for x in (Qp, Kp, V, dO)]
+
+
+def _run(xs, lam, lseg):
+    if lseg is not None:
+        os.environ["LA_LSEG"] = str(lseg)
+    try:
+        Qp, Kp, V, dO = [x.cuda() for x in xs]
+        O = binding.la_fwd_swish(Qp, Kp, V, lam)
+        dQp, dKp, dV = binding.la_bwd_swish(Qp, Kp, V, lam, dO)
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("LA_LSEG", None)
+    return [t.to(torch.float64).cpu().numpy() for t in (O, dQp, dKp, dV)]
+
+
+def _reference(xs, lam):
+    qp, kp, v, g = [x.to(torch.float64).numpy() for x in xs]
+    q, k = oracle.swish(qp), oracle.swish(kp)
+    O = oracle.c_recurrence_fwd(q, k, v, lam)
+    dQ, dK, dV = oracle.c_recurrence_bwd(q, k, v, lam, g)
+    return O, dQ * oracle.swish_grad(qp), dK * oracle.swish_grad(kp), dV
+
+
+@pytest.mark.parametrize("dtype,B,H,n,d,lseg", [
+    ("f32", 1, 2, 300, 64, None), ("f32", 2, 2, 300, 64, 128), ("f32", 1, 3, 200, 128, None),
+    ("f32", 1, 3, 200, 128, 64),
+    ("bf16", 2, 4, 1000, 128, None), ("bf16", 2, 4, 1000, 128, 256), ("bf16", 1, 3, 1, 128, None),
+    ("bf16", 2, 5, 700, 64, None), ("bf16", 2, 5, 700, 64, 192), ("bf16", 1, 16, 4096, 128, 1024),
+])
+def test_swish_attention_against_oracle(dtype, B, H, n, d, lseg):
+    assert torch.cuda.is_available()
+    lam = [1.0, 0.999, 0.97, 0.9, 0.5][:H] if H <= 5 else list(np.linspace(0.9, 1.0, H))
+    xs = _draw(B, H, n, d, dtype, seed=4000 + n + d)
+    got = _run(xs, lam, lseg)
+    ref = _reference(xs, lam)
+    for nm, x, r in zip(("O", "dQp", "dKp", "dV"), got, ref):
+        assert np.all(np.isfinite(x)), nm
+        err = oracle.rel_max_err(x, r)
+        assert err <= TOL[dtype], (nm, err)
+
+
+def test_fused_matches_activation_applied_outside():
+    """Feeding la_fwd / la_bwd the activated tensors (computed here in fp64 and rounded
+    to bf16) must give what the fused entry points give, up to the rounding of phi."""
+    lam = [1.0, 0.95, 0.7]
+    xs = _draw(2, 3, 640, 128, "bf16", seed=55)
+    fused = _run(xs, lam, None)
+    qp, kp = [x.to(torch.float64).numpy() for x in xs[:2]]
+    Q = torch.from_numpy(oracle.swish(qp)).to(torch.bfloat16).cuda()
+    K = torch.from_numpy(oracle.swish(kp)).to(torch.bfloat16).cuda()
+    V, dO = xs[2].cuda(), xs[3].cuda()
+    O = binding.la_fwd(Q, K, V, lam)
+    dQ, dK, dV = binding.la_bwd(Q, K, V, lam, dO)
+    torch.cuda.synchronize()
+    plain = [O.to(torch.float64).cpu().numpy(),
+             dQ.to(torch.float64).cpu().numpy() * oracle.swish_grad(qp),
+             dK.to(torch.float64).cpu().numpy() * oracle.swish_grad(kp),
+             dV.to(torch.float64).cpu().numpy()]
+    for nm, a, b in zip(("O", "dQp", "dKp", "dV"), fused, plain):
+        assert oracle.rel_max_err(a, b) <= 6e-3, nm
+
+
+def test_extreme_preactivations_stay_finite():
+    """phi and phi' at large |x| (exp overflow inside the sigmoid) give the limits, not NaN."""
+    xs = _draw(1, 2, 130, 64, "f32", seed=7)
+    xs[0][0, 0, :5] = torch.tensor([-200.0, -90.0, 90.0, 200.0, 0.0]).view(5, 1)
+    xs[1][0, 1, 3:6] = torch.tensor([-1e4, 1e4, -88.5]).view(3, 1)
+    lam = [0.9, 1.0]
+    got = _run(xs, lam, None)
+    ref = _reference(xs, lam)
+    for nm, x, r in zip(("O", "dQp", "dKp", "dV"), got, ref):
+        assert np.all(np.isfinite(x)), nm
+        assert oracle.rel_max_err(x, r) <= 1e-4, nm
