@@ -247,6 +247,22 @@ def main():
                  "bwd_GBps": round(5 * tensor_bytes / (gb * 1e-3) / 1e9, 1),
                  "note": "algorithmic bytes: 3 tensors forward, 5 backward; HBM-bound"}
 
+    # ---- Swish of the Q, K projections fused into the scans (next row) -------------------------
+    swish = []
+    for sB, sn in ((32, 2048), (1, TOKENS)):
+        t = views(sB, sn)
+        sf = _time(lambda: binding.la_fwd_swish(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=ws))
+        sb = _time(lambda: binding.la_bwd_swish(t["Q"], t["K"], t["V"], lam, t["dO"], dQp=t["dQ"], dKp=t["dK"],
+                                                dV=t["dV"], workspace=ws))
+        swish.append({"B": sB, "n": sn, "fwd_ms": round(sf, 4), "bwd_ms": round(sb, 4),
+                      "tokens_per_s": round(TOKENS / ((sf + sb) * 1e-3), 1),
+                      "algorithmic_GBps": round(16 * tensor_bytes / ((sf + sb) * 1e-3) / 1e9, 1)})
+    swish_fused = {"workload": "la_fwd_swish + la_bwd_swish, H=16, d=128, bf16, 65536 tokens",
+                   "points": swish,
+                   "note": "algorithmic bytes: 4 tensor passes forward, 12 backward (the two pre-activation "
+                           "tiles of the phi' epilogue are extra reads); separate activation kernels would "
+                           "add 10 passes to the plain path's 14"}
+
     total_tflops = value * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12
     out = {
         "metric": "fwd+bwd tokens/s (causal linear attention with decay, bf16, d=128, seq-len sweep "
@@ -265,6 +281,7 @@ def main():
         "roofline": roofline,
         "decode": decode,
         "gate_norm": gate_norm,
+        "swish_fused": swish_fused,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
