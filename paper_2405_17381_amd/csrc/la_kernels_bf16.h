@@ -239,16 +239,26 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
     // Rows past the segment end read the segment's last row instead (always in
     // bounds); they are zeroed when the block is staged, so that nothing here
     // consumes the loaded values and the loads stay in flight behind the compute.
+    // Tiles that no other workgroup reads are loaded with the non-temporal hint (they
+    // should not displace anything in L2): everything in a single-scan launch, the A
+    // operand in a paired launch, whose Bm and C tiles the partner workgroup reads too.
+    // (Measured: +3 % on the sweep; with the hint on the shared tiles as well, -6 %.)
     U4 ra[4], rb[4], rc[4];
+    const bool nt_all = launch.nroles == 1;
     auto load_block = [&](int blk) {
         const int t0 = seg_lo + blk * BK;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int t = t0 + 4 * sa + i;
             const size_t off = (size_t)min(t, seg_hi - 1) * D + 8 * sc;
-            rb[i] = *(const U4 *)(gB + off);
-            rc[i] = *(const U4 *)(gC + off);
-            ra[i] = *(const U4 *)(gA + off);
+            if (nt_all) {
+                rb[i] = __builtin_nontemporal_load((const U4 *)(gB + off));
+                rc[i] = __builtin_nontemporal_load((const U4 *)(gC + off));
+            } else {
+                rb[i] = *(const U4 *)(gB + off);
+                rc[i] = *(const U4 *)(gC + off);
+            }
+            ra[i] = __builtin_nontemporal_load((const U4 *)(gA + off));
         }
     };
     // ---- registers -> LDS, transposing C and the weighted Bm ---------------------
@@ -454,7 +464,8 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         if (ACT && (act & LA_ACT_OUT)) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                re[i] = *(const U4 *)(gE + (size_t)min(t0 + 4 * sa + i, seg_hi - 1) * D + 8 * sc);
+                re[i] = __builtin_nontemporal_load(
+                    (const U4 *)(gE + (size_t)min(t0 + 4 * sa + i, seg_hi - 1) * D + 8 * sc));
         }
         // ---- state update: St = lambda^BK St + (w Bm)^T C ---------------------------
 #pragma unroll
@@ -482,7 +493,7 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
                 U2 hi = *(const U2 *)(po + 8);
                 U4 out = {lo[0], lo[1], hi[0], hi[1]};
                 if (ACT && (act & LA_ACT_OUT)) out = mul_swish_grad_u4(out, re[i]);
-                if (t < seg_hi) *(U4 *)(gO + (size_t)t * D + 8 * sc) = out;
+                if (t < seg_hi) __builtin_nontemporal_store(out, (U4 *)(gO + (size_t)t * D + 8 * sc));
             }
         }
     }

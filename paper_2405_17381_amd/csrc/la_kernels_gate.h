@@ -21,17 +21,23 @@ struct GateArgs {
     float eps;
 };
 
+typedef uint32_t gate_u32x4 __attribute__((ext_vector_type(4)));
+
 // one 8-element chunk as loaded: 16 bytes (bf16) or 32 bytes (fp32)
 template <bool BF16>
 struct GateRaw {
     uint4 lo, hi;       // bf16 uses lo only
 };
 
-template <bool BF16>
+// NT: the chunk is read once and kept in registers (non-temporal hint)
+template <bool BF16, bool NT = false>
 __device__ __forceinline__ GateRaw<BF16> gate_fetch(const void *p, size_t idx)
 {
     GateRaw<BF16> r;
-    if (BF16) {
+    if (BF16 && NT) {
+        const gate_u32x4 v = __builtin_nontemporal_load((const gate_u32x4 *)((const uint16_t *)p + idx));
+        r.lo = make_uint4(v[0], v[1], v[2], v[3]);
+    } else if (BF16) {
         r.lo = *(const uint4 *)((const uint16_t *)p + idx);
     } else {
         r.lo = *(const uint4 *)((const float *)p + idx);
@@ -80,7 +86,8 @@ __device__ __forceinline__ void gate_store8(void *p, size_t idx, const float (&x
         r.y = gate_bf16_rne(x[2]) | (gate_bf16_rne(x[3]) << 16);
         r.z = gate_bf16_rne(x[4]) | (gate_bf16_rne(x[5]) << 16);
         r.w = gate_bf16_rne(x[6]) | (gate_bf16_rne(x[7]) << 16);
-        *(uint4 *)((uint16_t *)p + idx) = r;
+        const gate_u32x4 v = {r.x, r.y, r.z, r.w};       // results are not read again here
+        __builtin_nontemporal_store(v, (gate_u32x4 *)((uint16_t *)p + idx));
     } else {
         *(float4 *)((float *)p + idx) = make_float4(x[0], x[1], x[2], x[3]);
         *(float4 *)((float *)p + idx + 4) = make_float4(x[4], x[5], x[6], x[7]);
@@ -114,9 +121,9 @@ __global__ __launch_bounds__(256) void la_gate_norm_kernel(GateArgs a)
         for (int k = 0; k < KC; ++k) {    // issue every cached load before using any
             const int h = hh + HPS * k;
             if (h < a.H) {
-                co[k] = gate_fetch<BF16>(a.O, index(h));
-                cu[k] = gate_fetch<BF16>(a.U, index(h));
-                if (BWD) cg[k] = gate_fetch<BF16>(a.dY, index(h));
+                co[k] = gate_fetch<BF16, true>(a.O, index(h));
+                cu[k] = gate_fetch<BF16, true>(a.U, index(h));
+                if (BWD) cg[k] = gate_fetch<BF16, true>(a.dY, index(h));
             }
         }
 #pragma unroll

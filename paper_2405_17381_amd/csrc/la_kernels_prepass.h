@@ -90,8 +90,8 @@ __global__ __launch_bounds__(D * 2, 2) void la_prepass_bf16(ScanLaunch launch, L
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const size_t off = (size_t)min(t0 + 4 * sa + i, seg_hi - 1) * D + 8 * sc;
-            rb_all[slot][i] = *(const U4 *)(gB + off);
-            rc_all[slot][i] = *(const U4 *)(gC + off);
+            rb_all[slot][i] = __builtin_nontemporal_load((const U4 *)(gB + off));
+            rc_all[slot][i] = __builtin_nontemporal_load((const U4 *)(gC + off));
         }
     };
 
