@@ -341,8 +341,9 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
             lamBK = pw(m);
         }
         stage_block(t0);
-        __syncthreads();
+        // the registers are free again: prefetch before waiting for the other waves
         if (ib + 1 < nblk) load_block(rev ? blk - 1 : blk + 1);
+        __syncthreads();
 
         U4 cf[KS_B];                            // C^T fragments of this wave's slice
         auto load_cf = [&]() {
