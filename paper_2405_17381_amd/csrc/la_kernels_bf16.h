@@ -245,6 +245,9 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
     // (Measured: +3 % on the sweep; with the hint on the shared tiles as well, -6 %.)
     U4 ra[4], rb[4], rc[4];
     const bool nt_all = launch.nroles == 1;
+    // (paired launch with the Swish epilogue: the dV scan's A operand is the tile whose
+    // phi' the dK scan needs a little later)
+    const bool nt_a = nt_all || !(ACT && role == 1);
     auto load_block = [&](int blk) {
         const int t0 = seg_lo + blk * BK;
 #pragma unroll
@@ -258,7 +261,8 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
                 rb[i] = *(const U4 *)(gB + off);
                 rc[i] = *(const U4 *)(gC + off);
             }
-            ra[i] = __builtin_nontemporal_load((const U4 *)(gA + off));
+            if (nt_a) ra[i] = __builtin_nontemporal_load((const U4 *)(gA + off));
+            else ra[i] = *(const U4 *)(gA + off);
         }
     };
     // ---- registers -> LDS, transposing C and the weighted Bm ---------------------
@@ -465,8 +469,10 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         if (ACT && (act & LA_ACT_OUT)) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                re[i] = __builtin_nontemporal_load(
-                    (const U4 *)(gE + (size_t)min(t0 + 4 * sa + i, seg_hi - 1) * D + 8 * sc));
+            {
+                const U4 *pe = (const U4 *)(gE + (size_t)min(t0 + 4 * sa + i, seg_hi - 1) * D + 8 * sc);
+                re[i] = nt_all ? __builtin_nontemporal_load(pe) : *pe;
+            }
         }
         // ---- state update: St = lambda^BK St + (w Bm)^T C ---------------------------
 #pragma unroll
