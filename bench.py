@@ -79,6 +79,7 @@ def main():
                          "whose FETCH_SIZE / WRITE_SIZE readings calibrate the HBM counters")
     args = ap.parse_args()
     global POINTS
+    all_points = list(POINTS)
     if args.point:
         POINTS = [(B, n) for (B, n) in POINTS if n == args.point]
         assert POINTS, "no sweep point with n=%d" % args.point
@@ -105,7 +106,7 @@ def main():
     flat["dO"] = torch.randn(numel, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
     for name in ("O", "dQ", "dK", "dV"):
         flat[name] = torch.empty(numel, device=dev, dtype=torch.bfloat16)
-    ws_bytes = max(binding.la_workspace_bytes(B, H, n, D, binding.LA_BF16, True) for B, n in POINTS)
+    ws_bytes = max(binding.la_workspace_bytes(B, H, n, D, binding.LA_BF16, True) for B, n in all_points)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
 
     def views(B, n):
