@@ -57,7 +57,7 @@ Plan make_plan(int B, int H, int n, int d, la_dtype dt)
     // tuning / test override: segment length in tokens
     if (const char *e = std::getenv("LA_LSEG")) {
         long v = std::atol(e);
-        if (v > 0) {
+        if (v > 0 && scans <= 65535) {          // the segment scan's grid has one row per scan
             v = round_up((int)(v > (1 << 30) ? (1 << 30) : v), p.tile);
             L = (int)(v < round_up(n, p.tile) ? v : round_up(n, p.tile));
         }
@@ -234,14 +234,29 @@ int run_prepass(const ScanArgs *a, int nroles, const LaLambdas &lams, long scans
 }
 
 // Exclusive scan over the segments, in place: local states -> entering states.
+SegScanArgs segment_scan_args(const ScanArgs &a, bool rev, int d)
+{
+    SegScanArgs sa;
+    sa.states = a.states; sa.init = rev ? nullptr : a.st_in; sa.skip_bits = a.skip_bits;
+    sa.H = a.H; sa.S = a.S; sa.L = a.L; sa.DD = d * d;
+    return sa;
+}
+
 template <bool REV>
 int run_segment_scan(const ScanArgs &a, const LaLambdas &lams, long scans, int d, hipStream_t s)
 {
-    SegScanArgs sa;
-    sa.states = a.states; sa.init = REV ? nullptr : a.st_in; sa.skip_bits = a.skip_bits;
-    sa.H = a.H; sa.S = a.S; sa.L = a.L; sa.DD = d * d;
     dim3 grid((unsigned)((d * d / 4 + 255) / 256), (unsigned)scans), block(256);
-    hipLaunchKernelGGL(la_segment_scan<REV>, grid, block, 0, s, sa, lams);
+    hipLaunchKernelGGL(la_segment_scan<REV>, grid, block, 0, s, segment_scan_args(a, REV, d), lams);
+    return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
+// The backward pass's forward and reverse segment scans as one launch.
+int run_segment_scan_pair(const ScanArgs &f, const ScanArgs &r, const LaLambdas &lams, long scans, int d,
+                          hipStream_t s)
+{
+    dim3 grid((unsigned)((d * d / 4 + 255) / 256), (unsigned)scans, 2), block(256);
+    hipLaunchKernelGGL(la_segment_scan_pair, grid, block, 0, s, segment_scan_args(f, false, d),
+                       segment_scan_args(r, true, d), lams);
     return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 
@@ -324,8 +339,7 @@ int run_backward(const void *Q, const void *K, const void *V, const void *dO, vo
     }
     if (p.S > 1) {
         int rc = run_prepass(pre, 2, lams, scans, d, dt, s);
-        if (rc == LA_OK) rc = run_segment_scan<false>(pre[0], lams, scans, d, s);
-        if (rc == LA_OK) rc = run_segment_scan<true>(pre[1], lams, scans, d, s);
+        if (rc == LA_OK) rc = run_segment_scan_pair(pre[0], pre[1], lams, scans, d, s);
         if (rc != LA_OK) return rc;
     }
     int rc = run_block_scan<false>(pre[0], lams, scans, d, dt, s);

@@ -10,7 +10,7 @@
 // loads of a batch of eight segments are issued together (they do not depend
 // on the carry), only the stores follow the recurrence.
 template <bool REV>
-__global__ __launch_bounds__(256) void la_segment_scan(SegScanArgs a, LaLambdas lams)
+__device__ __forceinline__ void segment_scan_body(const SegScanArgs &a, const LaLambdas &lams)
 {
     const int scan = blockIdx.y;
     const int e = (blockIdx.x * 256 + threadIdx.x) * 4;
@@ -44,6 +44,20 @@ __global__ __launch_bounds__(256) void la_segment_scan(SegScanArgs a, LaLambdas 
             }
         }
     }
+}
+
+template <bool REV>
+__global__ __launch_bounds__(256) void la_segment_scan(SegScanArgs a, LaLambdas lams)
+{
+    segment_scan_body<REV>(a, lams);
+}
+
+// The backward pass's two segment scans (forward states of one scan, reverse states
+// of another) in one launch: blockIdx.z selects.
+__global__ __launch_bounds__(256) void la_segment_scan_pair(SegScanArgs fwd, SegScanArgs rev, LaLambdas lams)
+{
+    if (blockIdx.z == 0) segment_scan_body<false>(fwd, lams);
+    else segment_scan_body<true>(rev, lams);
 }
 
 // One token of the recurrence for every (batch, head) (App. A, recurrence form):
