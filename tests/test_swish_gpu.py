@@ -94,3 +94,27 @@ def test_extreme_preactivations_stay_finite():
     for nm, x, r in zip(("O", "dQp", "dKp", "dV"), got, ref):
         assert np.all(np.isfinite(x)), nm
         assert oracle.rel_max_err(x, r) <= 1e-4, nm
+
+
+def test_swish_at_the_benchmark_point_sampled():
+    """The (B=1, n=65536) sweep point, H=16, d=128, bf16, default plan (32 segments of 2048 tokens):
+    two whole (batch, head) scans are compared with the oracle, the fastest and the slowest decay."""
+    from paper_2405_17381_amd import synth
+    w = synth.workload("c3_65536")
+    g = torch.Generator(device="cuda").manual_seed(synth.BASE_SEED + 77)
+    shape = (w.B, w.H, w.n, w.d)
+    Qp, Kp, V, dO = [torch.randn(shape, generator=g, device="cuda") for _ in range(4)]
+    V = V / w.d
+    Qp, Kp, V, dO = [x.to(torch.bfloat16) for x in (Qp, Kp, V, dO)]
+    O = binding.la_fwd_swish(Qp, Kp, V, w.lambdas)
+    dQp, dKp, dV = binding.la_bwd_swish(Qp, Kp, V, w.lambdas, dO)
+    torch.cuda.synchronize()
+    for t in (O, dQp, dKp, dV):
+        assert torch.isfinite(t.float()).all()
+    for h in (0, w.H - 1):
+        xs = [x[0, h].to(torch.float64).cpu()[None, None] for x in (Qp, Kp, V, dO)]
+        ref = _reference(xs, [w.lambdas[h]])
+        for nm, x, r in zip(("O", "dQp", "dKp", "dV"), (O, dQp, dKp, dV), ref):
+            got = x[0, h].to(torch.float64).cpu().numpy()[None, None]
+            err = oracle.rel_max_err(got, r)
+            assert err <= TOL["bf16"], (h, nm, err)
