@@ -350,6 +350,8 @@ int run_backward(const void *Q, const void *K, const void *V, const void *dO, vo
 int check_workspace(const Plan &p, int B, int H, int d, void *workspace, size_t workspace_bytes,
                     bool is_bwd)
 {
+    // one workgroup per (scan, segment), two in a paired launch: keep the grid within 2^31
+    if ((long)B * H * p.S > (1L << 29)) return LA_ERR_SHAPE;
     const size_t need = state_bytes(p, B, H, d) * (is_bwd ? 2 : 1);
     if (need == 0) return LA_OK;
     if (workspace == nullptr || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < need)

@@ -85,6 +85,9 @@ def test_bad_arguments_are_rejected_without_a_gpu(monkeypatch):
     lam_arr = (ctypes.c_float * 1)(0.5)
     assert lib.la_bwd(4096, 4096, 4096, lam_arr, 4096, 4096, 4096, 0,
                       1, 1, 8, 64, 1, 0, 0, None) == -1
+    # more (scan, segment) workgroups than a grid can hold
+    lam16 = (ctypes.c_float * 16)(*([0.5] * 16))
+    assert lib.la_fwd(4096, 4096, 4096, lam16, 4096, 4000, 16, 1 << 20, 64, 1, 4096, 1 << 62, None) == -2
 
 
 def test_binding_refuses_cpu_tensors():
