@@ -58,9 +58,11 @@ def decay_matrix(n: int, lam: float) -> np.ndarray:
 # form (i): quadratic masked form
 # --------------------------------------------------------------------------
 def left_product_fwd(Q, K, V, lam):
+    """Q, K: [B, H, n, d_k]; V: [B, H, n, d_v] (d_k = d_v in the paper's layers; a wider
+    query / key feature, as the cos / sin features of LRPE-d give, changes nothing here)."""
     Q, K, V = _as64(Q), _as64(K), _as64(V)
     B, H, n, d = Q.shape
-    O = np.empty_like(Q)
+    O = np.empty_like(V)
     for h in range(H):
         A = decay_matrix(n, lam[h])
         for b in range(B):
@@ -73,8 +75,8 @@ def left_product_bwd(Q, K, V, lam, dO):
     Q, K, V, dO = _as64(Q), _as64(K), _as64(V), _as64(dO)
     B, H, n, d = Q.shape
     dQ = np.empty_like(Q)
-    dK = np.empty_like(Q)
-    dV = np.empty_like(Q)
+    dK = np.empty_like(K)
+    dV = np.empty_like(V)
     for h in range(H):
         A = decay_matrix(n, lam[h])
         for b in range(B):
@@ -96,12 +98,13 @@ def recurrence_fwd(Q, K, V, lam, kv0=None, return_state=False):
     state after the last token, kv_n, is returned as well."""
     Q, K, V = _as64(Q), _as64(K), _as64(V)
     B, H, n, d = Q.shape
-    O = np.empty_like(Q)
-    KVn = np.empty((B, H, d, d), dtype=np.float64)
+    dv = V.shape[3]
+    O = np.empty_like(V)
+    KVn = np.empty((B, H, d, dv), dtype=np.float64)
     for b in range(B):
         for h in range(H):
             l = float(lam[h])
-            kv = np.zeros((d, d), dtype=np.float64) if kv0 is None else _as64(kv0)[b, h].copy()
+            kv = np.zeros((d, dv), dtype=np.float64) if kv0 is None else _as64(kv0)[b, h].copy()
             for t in range(n):
                 kv = l * kv + np.outer(K[b, h, t], V[b, h, t])
                 O[b, h, t] = Q[b, h, t] @ kv
@@ -126,17 +129,18 @@ def decode_step(q, k, v, lam, kv):
 def recurrence_bwd(Q, K, V, lam, dO):
     Q, K, V, dO = _as64(Q), _as64(K), _as64(V), _as64(dO)
     B, H, n, d = Q.shape
+    dv = V.shape[3]
     dQ = np.empty_like(Q)
-    dK = np.empty_like(Q)
-    dV = np.empty_like(Q)
+    dK = np.empty_like(K)
+    dV = np.empty_like(V)
     for b in range(B):
         for h in range(H):
             l = float(lam[h])
-            kv = np.zeros((d, d), dtype=np.float64)
+            kv = np.zeros((d, dv), dtype=np.float64)
             for t in range(n):
                 kv = l * kv + np.outer(K[b, h, t], V[b, h, t])
                 dQ[b, h, t] = kv @ dO[b, h, t]
-            dkv = np.zeros((d, d), dtype=np.float64)
+            dkv = np.zeros((d, dv), dtype=np.float64)
             for t in range(n - 1, -1, -1):
                 dkv = l * dkv + np.outer(Q[b, h, t], dO[b, h, t])
                 dK[b, h, t] = dkv @ V[b, h, t]
@@ -213,3 +217,33 @@ def swish_attention_bwd(Qp, Kp, V, lam, dO):
     dQp = dQ * phi'(Qp), dKp = dK * phi'(Kp); dV is the attention's own."""
     dQ, dK, dV = recurrence_bwd(swish(Qp), swish(Kp), V, lam, dO)
     return dQ * swish_grad(Qp), dK * swish_grad(Kp), dV
+
+
+# --------------------------------------------------------------------------
+# LRPE-d (Sec. 4.1, "Position Encoding"):  a_ts = q_t^T k_s lambda^(t-s) exp(i theta (t-s)).
+# Readings: theta is one angle per head and feature ([H, d]); the attention score is the
+# real part,  sum_i q_ti k_si cos(theta_i (t - s));  positions count from 0 (only the
+# differences t - s enter).
+# --------------------------------------------------------------------------
+def lrpe_fwd(Q, K, V, lam, theta):
+    """The definition written out: O[t] = sum_{s<=t} lambda^(t-s) [sum_i q_ti k_si cos(theta_i (t-s))] v_s."""
+    Q, K, V, theta = _as64(Q), _as64(K), _as64(V), _as64(theta)
+    B, H, n, d = Q.shape
+    O = np.zeros_like(V)
+    for b in range(B):
+        for h in range(H):
+            for t in range(n):
+                for s in range(t + 1):
+                    score = np.sum(Q[b, h, t] * K[b, h, s] * np.cos(theta[h] * (t - s)))
+                    O[b, h, t] += float(lam[h]) ** (t - s) * score * V[b, h, s]
+    return O
+
+
+def lrpe_features(X, theta):
+    """The decomposition the paper points to ("can be decomposed with respect to s and t
+    separately"): x_t -> [x_t cos(t theta), x_t sin(t theta)], so that the plain inner
+    product of two feature rows is sum_i x_ti y_si cos(theta_i (t - s))."""
+    X, theta = _as64(X), _as64(theta)
+    B, H, n, d = X.shape
+    ang = np.arange(n, dtype=np.float64)[None, :, None] * theta[:, None, :]      # [H, n, d]
+    return np.concatenate([X * np.cos(ang)[None], X * np.sin(ang)[None]], axis=3)

@@ -387,3 +387,72 @@ def test_swish_attention_gradients_by_finite_differences():
     O = oracle.swish_attention_fwd(Qp, Kp, V, lam)
     np.testing.assert_allclose(O, oracle.left_product_fwd(oracle.swish(Qp), oracle.swish(Kp), V, lam), rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(oracle.swish_attention_fwd(Qp, Kp, 2.0 * V, lam), 2.0 * O, rtol=1e-12)
+
+
+# ---- 13. wider query / key features and LRPE-d (Sec. 4.1) ------------------------------
+def test_wide_keys_are_a_sum_over_feature_slices():
+    """With d_k = 2 d_v the scores add over the two halves of the features, so the
+    attention (both forms) is the sum of two ordinary ones, and so is dV; dQ, dK split."""
+    rng = np.random.default_rng(21)
+    B, H, n, dv = 1, 2, 9, 3
+    lam = [0.7, 1.0]
+    Qw, Kw = rng.standard_normal((B, H, n, 2 * dv)), rng.standard_normal((B, H, n, 2 * dv))
+    V, dO = rng.standard_normal((B, H, n, dv)), rng.standard_normal((B, H, n, dv))
+    O = oracle.left_product_fwd(Qw, Kw, V, lam)
+    np.testing.assert_allclose(O, oracle.recurrence_fwd(Qw, Kw, V, lam), rtol=1e-12, atol=1e-13)
+    parts = [oracle.left_product_fwd(Qw[..., j * dv:(j + 1) * dv], Kw[..., j * dv:(j + 1) * dv], V, lam) for j in (0, 1)]
+    np.testing.assert_allclose(O, parts[0] + parts[1], rtol=1e-12, atol=1e-13)
+    dQw, dKw, dV = oracle.left_product_bwd(Qw, Kw, V, lam, dO)
+    r = oracle.recurrence_bwd(Qw, Kw, V, lam, dO)
+    for a, b in zip((dQw, dKw, dV), r):
+        np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-13)
+    dv_sum = np.zeros_like(dV)
+    for j in (0, 1):
+        sl = slice(j * dv, (j + 1) * dv)
+        g = oracle.left_product_bwd(Qw[..., sl], Kw[..., sl], V, lam, dO)
+        np.testing.assert_allclose(dQw[..., sl], g[0], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(dKw[..., sl], g[1], rtol=1e-12, atol=1e-13)
+        dv_sum += g[2]
+    np.testing.assert_allclose(dV, dv_sum, rtol=1e-12, atol=1e-13)
+    # finite differences of <dO, O> with respect to one entry of each wide operand
+    h = 1e-6
+    loss = lambda q, k, v: float(np.sum(dO * oracle.left_product_fwd(q, k, v, lam)))
+    for which, grad in ((0, dQw), (1, dKw), (2, dV)):
+        for idx in [(0, 0, 0, 0), (0, 1, 4, 2), (0, 1, n - 1, grad.shape[3] - 1)]:
+            a = [Qw.copy(), Kw.copy(), V.copy()]
+            b = [Qw.copy(), Kw.copy(), V.copy()]
+            a[which][idx] += h
+            b[which][idx] -= h
+            assert abs((loss(*a) - loss(*b)) / (2 * h) - grad[idx]) <= 1e-7 * max(1.0, abs(grad[idx]))
+
+
+def test_lrpe_definition_equals_attention_over_rotated_features():
+    """The score q_t^T k_s lambda^(t-s) Re exp(i theta (t-s)), written out term by term,
+    equals the ordinary (wide) attention over the cos / sin features."""
+    rng = np.random.default_rng(22)
+    B, H, n, d = 1, 2, 7, 3
+    lam = [0.8, 1.0]
+    theta = rng.uniform(0.0, 2.0, size=(H, d))
+    Q, K, V = (rng.standard_normal((B, H, n, d)) for _ in range(3))
+    O_def = oracle.lrpe_fwd(Q, K, V, lam, theta)
+    Qw, Kw = oracle.lrpe_features(Q, theta), oracle.lrpe_features(K, theta)
+    assert Qw.shape == (B, H, n, 2 * d)
+    np.testing.assert_allclose(oracle.left_product_fwd(Qw, Kw, V, lam), O_def, rtol=1e-12, atol=1e-13)
+    # theta = 0: no rotation, the plain attention
+    zero = np.zeros((H, d))
+    np.testing.assert_allclose(oracle.lrpe_fwd(Q, K, V, lam, zero), oracle.left_product_fwd(Q, K, V, lam),
+                               rtol=1e-12, atol=1e-13)
+    # one feature, constant q = k = v = 1, lambda = 1: O[t] = sum_{m=0..t} cos(m theta)  (Dirichlet kernel sum)
+    th = 0.37
+    one = np.ones((1, 1, 6, 1))
+    O1 = oracle.lrpe_fwd(one, one, one, [1.0], np.array([[th]]))
+    closed = np.array([np.sin((t + 1) * th / 2) * np.cos(t * th / 2) / np.sin(th / 2) for t in range(6)])
+    np.testing.assert_allclose(O1.ravel(), closed, rtol=1e-12)
+    # only differences of positions matter: dropping the first token of a sequence whose first
+    # key/value row is zero leaves the later outputs unchanged
+    K0, V0 = K.copy(), V.copy()
+    K0[:, :, 0] = 0.0
+    V0[:, :, 0] = 0.0
+    full = oracle.lrpe_fwd(Q, K0, V0, lam, theta)
+    cut = oracle.lrpe_fwd(Q[:, :, 1:], K0[:, :, 1:], V0[:, :, 1:], lam, theta)
+    np.testing.assert_allclose(full[:, :, 1:], cut, rtol=1e-12, atol=1e-13)
