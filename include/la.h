@@ -178,6 +178,32 @@ int la_bwd_swish(const void *Qp, const void *Kp, const void *V,
                  int B, int H, int n, int d, la_dtype dt,
                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Attention whose query / key feature is wider than its value feature, d_k = m d_v
+ * (m = 1..4), as the cos / sin features of LRPE-d give (Sec. 4.1, "Position
+ * Encoding": the score q_t^T k_s lambda^(t-s) exp(i theta (t-s)) "can be decomposed
+ * with respect to s and t": with x~_t = [x_t cos(t theta), x_t sin(t theta)] it is the
+ * plain score q~_t^T k~_s lambda^(t-s) over 2d features):
+ *     O[t] = sum_{s <= t} lambda^(t-s) (Qw[t] . Kw[s]) V[s]
+ * and its gradients.  Qw, Kw, dQw, dKw: [B, H, n, dk]; V, O, dO, dV: [B, H, n, dv];
+ * dv is 64 or 128.  The scores add over the m slices of dv features, so the result
+ * is accumulated over m scans of slices (the KV state is m states of dv x dv); O and
+ * dV are read back and rounded to dt between slices.  Workspace as la_fwd / la_bwd
+ * with d = dv.  The rotation itself (and theta's gradient) is the caller's.
+ */
+int la_fwd_wide(const void *Qw, const void *Kw, const void *V,
+                const float *lambda /* host, [H] */,
+                void *O,
+                int B, int H, int n, int dk, int dv, la_dtype dt,
+                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+int la_bwd_wide(const void *Qw, const void *Kw, const void *V,
+                const float *lambda /* host, [H] */,
+                const void *dO,
+                void *dQw, void *dKw, void *dV,
+                int B, int H, int n, int dk, int dv, la_dtype dt,
+                void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static, human-readable text for an la_status value. */
 const char *la_strerror(int status);
 

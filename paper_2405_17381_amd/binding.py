@@ -16,7 +16,8 @@ LA_F32, LA_BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libla.so")
 EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_fwd_state", "la_decode_step", "la_gate_norm_fwd",
-           "la_gate_norm_bwd", "la_fwd_swish", "la_bwd_swish", "la_strerror", "la_plan",
+           "la_gate_norm_bwd", "la_fwd_swish", "la_bwd_swish", "la_fwd_wide", "la_bwd_wide", "la_strerror",
+           "la_plan",
            "la_profile_enable", "la_profile_collect")
 _lib = None
 
@@ -47,6 +48,10 @@ def load_library():
     lib.la_fwd_swish.restype = ci
     lib.la_bwd_swish.argtypes = lib.la_bwd.argtypes
     lib.la_bwd_swish.restype = ci
+    lib.la_fwd_wide.argtypes = [vp, vp, vp, fp, vp, ci, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.la_fwd_wide.restype = ci
+    lib.la_bwd_wide.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.la_bwd_wide.restype = ci
     lib.la_fwd_state.argtypes = [vp, vp, vp, fp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.la_fwd_state.restype = ci
     lib.la_decode_step.argtypes = [vp, vp, vp, fp, vp, vp, ci, ci, ci, ci, vp]
@@ -222,6 +227,52 @@ def la_bwd(Q, K, V, lam, dO, dQ=None, dK=None, dV=None, workspace: Optional[torc
 def la_bwd_swish(Qp, Kp, V, lam, dO, dQp=None, dKp=None, dV=None, workspace: Optional[torch.Tensor] = None):
     """Gradients of la_fwd_swish with respect to the pre-activations Qp, Kp and to V."""
     return la_bwd(Qp, Kp, V, lam, dO, dQ=dQp, dK=dKp, dV=dV, workspace=workspace, _entry="la_bwd_swish")
+
+
+def la_fwd_wide(Qw, Kw, V, lam, O=None, workspace: Optional[torch.Tensor] = None):
+    """O = attention(Qw, Kw, V, lambda) with Qw, Kw [B,H,n,dk] and V [B,H,n,dv], dk a multiple of dv."""
+    _check([Qw, Kw])
+    _check([V])
+    B, H, n, dv = V.shape
+    dk = Qw.shape[3]
+    if Qw.shape[:3] != V.shape[:3] or Qw.dtype != V.dtype:
+        raise ValueError("Qw / Kw and V disagree in batch, heads, length or dtype")
+    O = torch.empty_like(V) if O is None else O
+    _check([V, O])
+    dt = _dt(V)
+    ws, ws_ptr, ws_bytes = _workspace(B, H, n, dv, dt, False, V.device, workspace)
+    with torch.cuda.device(V.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_fwd_wide(Qw.data_ptr(), Kw.data_ptr(), V.data_ptr(), _lam(lam, H), O.data_ptr(),
+                                        B, H, n, dk, dv, dt, ws_ptr, ws_bytes, stream)
+    if rc != 0:
+        raise LaError(rc, "la_fwd_wide")
+    return O
+
+
+def la_bwd_wide(Qw, Kw, V, lam, dO, dQw=None, dKw=None, dV=None, workspace: Optional[torch.Tensor] = None):
+    """(dQw, dKw, dV) of la_fwd_wide."""
+    _check([Qw, Kw])
+    _check([V, dO])
+    B, H, n, dv = V.shape
+    dk = Qw.shape[3]
+    if Qw.shape[:3] != V.shape[:3] or Qw.dtype != V.dtype:
+        raise ValueError("Qw / Kw and V disagree in batch, heads, length or dtype")
+    dQw = torch.empty_like(Qw) if dQw is None else dQw
+    dKw = torch.empty_like(Qw) if dKw is None else dKw
+    dV = torch.empty_like(V) if dV is None else dV
+    _check([Qw, dQw, dKw])
+    _check([V, dV])
+    dt = _dt(V)
+    ws, ws_ptr, ws_bytes = _workspace(B, H, n, dv, dt, True, V.device, workspace)
+    with torch.cuda.device(V.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_bwd_wide(Qw.data_ptr(), Kw.data_ptr(), V.data_ptr(), _lam(lam, H), dO.data_ptr(),
+                                        dQw.data_ptr(), dKw.data_ptr(), dV.data_ptr(),
+                                        B, H, n, dk, dv, dt, ws_ptr, ws_bytes, stream)
+    if rc != 0:
+        raise LaError(rc, "la_bwd_wide")
+    return dQw, dKw, dV
 
 
 def la_gate_norm_fwd(O, U, eps: float = 0.0, Y=None):

@@ -200,10 +200,25 @@ hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
     return launch_f32<128, 32, REV, STATE_ONLY>(a, lams, s);
 }
 
+LaLayout contiguous_layout(int H, int n, int d)
+{
+    LaLayout l;
+    l.bs = (long)H * n * d; l.hs = (long)n * d; l.ld = d;
+    return l;
+}
+
+// How the query / key operands of a call differ from plain contiguous [B, H, n, d] tensors.
+struct Variant {
+    bool swish = false;     // Q, K are pre-activations (la_fwd_swish / la_bwd_swish)
+    int wide_ld = 0;        // > 0: Q, K (and dQ, dK) are d-wide slices of rows this many elements wide
+    bool accumulate = false; // the result over this slice is added to O (forward) / dV (backward)
+};
+
 ScanArgs make_args(const void *A, const void *Bm, const void *C, void *Out, const Plan &p,
-                   int H, int n, la_dtype dt, float *states, int transpose_init)
+                   int H, int n, int d, la_dtype dt, float *states, int transpose_init)
 {
     ScanArgs a;
+    a.lA = a.lB = a.lC = a.lO = a.lE = contiguous_layout(H, n, d);
     a.A = A; a.Bm = Bm; a.C = C; a.Out = Out;
     a.states = p.S > 1 ? states : nullptr;
     a.n = n; a.H = H; a.L = p.L; a.S = p.S;
@@ -273,11 +288,16 @@ int run_block_scan(const ScanArgs &a, const LaLambdas &lams, long scans, int d, 
 template <bool REV>
 int run_scan(const void *A, const void *Bm, const void *C, void *Out, const LaLambdas &lams,
              const Plan &p, int B, int H, int n, int d, la_dtype dt, float *states, hipStream_t s,
-             const float *st_in = nullptr, float *st_out = nullptr, int act = 0)
+             const float *st_in = nullptr, float *st_out = nullptr, const Variant &var = Variant())
 {
     const long scans = (long)B * H;
-    ScanArgs a = make_args(A, Bm, C, Out, p, H, n, dt, states, 0);
-    a.act = act;
+    ScanArgs a = make_args(A, Bm, C, Out, p, H, n, d, dt, states, 0);
+    // forward use only (O = scan(Q, K, V)): A and Bm are the query / key operands
+    if (var.swish) a.act |= LA_ACT_A | LA_ACT_BM;
+    if (var.wide_ld > 0) {
+        a.lA = a.lB = contiguous_layout(H, n, var.wide_ld);
+        a.act |= LA_ACT_EXT | (var.accumulate ? LA_ACT_ACC : 0);
+    }
     a.B = B;
     a.rev = REV ? 1 : 0;
     a.st_in = st_in;
@@ -320,22 +340,31 @@ int run_reverse_pair(const ScanArgs &ak, const ScanArgs &av, const LaLambdas &la
 // operand, and dQ, dK are multiplied by phi'(Q), phi'(K) as they are stored.
 int run_backward(const void *Q, const void *K, const void *V, const void *dO, void *dQ, void *dK,
                  void *dV, const LaLambdas &lams, const Plan &p, int B, int H, int n, int d,
-                 la_dtype dt, float *ws, hipStream_t s, bool swish)
+                 la_dtype dt, float *ws, hipStream_t s, const Variant &var)
 {
     const long scans = (long)B * H;
     float *ws_f = ws;
     float *ws_r = ws ? ws + (size_t)scans * p.S * (size_t)d * d : nullptr;
     ScanArgs pre[2];
-    pre[0] = make_args(dO, V, K, dQ, p, H, n, dt, ws_f, 0);
-    pre[1] = make_args(V, dO, Q, dK, p, H, n, dt, ws_r, 0);
+    pre[0] = make_args(dO, V, K, dQ, p, H, n, d, dt, ws_f, 0);
+    pre[1] = make_args(V, dO, Q, dK, p, H, n, d, dt, ws_r, 0);
     pre[1].rev = 1;
     pre[0].B = pre[1].B = B;
-    ScanArgs av = make_args(K, Q, dO, dV, p, H, n, dt, ws_r, 1);
+    ScanArgs av = make_args(K, Q, dO, dV, p, H, n, d, dt, ws_r, 1);
     av.rev = 1;
-    if (swish) {
+    if (var.swish) {
         pre[0].act = LA_ACT_C | LA_ACT_OUT; pre[0].E = Q;      // dQ = scan(dO, V, phi(K)) * phi'(Q)
         pre[1].act = LA_ACT_C | LA_ACT_OUT; pre[1].E = K;      // dK = scan_rev(V, dO, phi(Q)) * phi'(K)
         av.act = LA_ACT_A | LA_ACT_BM;                         // dV = scan_rev(phi(K), phi(Q), dO)
+    }
+    if (var.wide_ld > 0) {
+        // Q, K, dQ, dK are d-wide slices of wider rows; dV sums over the slices
+        const LaLayout w = contiguous_layout(H, n, var.wide_ld);
+        pre[0].lC = pre[0].lO = w;                             // dQ slice = scan(dO, V, K slice)
+        pre[1].lC = pre[1].lO = w;                             // dK slice = scan_rev(V, dO, Q slice)
+        av.lA = av.lB = w;                                     // dV (+)= scan_rev(K slice, Q slice, dO)
+        pre[0].act |= LA_ACT_EXT; pre[1].act |= LA_ACT_EXT;
+        av.act |= LA_ACT_EXT | (var.accumulate ? LA_ACT_ACC : 0);
     }
     if (p.S > 1) {
         int rc = run_prepass(pre, 2, lams, scans, d, dt, s);
@@ -376,7 +405,7 @@ int run_gate_norm(const GateArgs &g, int B, int n, int d, la_dtype dt, hipStream
 // Argument checks and planning shared by the forward entry points.
 int forward(const void *Q, const void *K, const void *V, const float *lambda, void *O,
             const float *kv_in, float *kv_out, int B, int H, int n, int d, la_dtype dt,
-            void *workspace, size_t workspace_bytes, void *hip_stream, int act)
+            void *workspace, size_t workspace_bytes, void *hip_stream, const Variant &var)
 {
     int rc = check_common(B, H, n, d, dt);
     if (rc != LA_OK) return rc;
@@ -391,13 +420,13 @@ int forward(const void *Q, const void *K, const void *V, const float *lambda, vo
     if (rc != LA_OK) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
     // O = scan(Q, K, V)                                                   (Alg. 5)
-    return run_scan<false>(Q, K, V, O, lams, p, B, H, n, d, dt, (float *)workspace, s, kv_in, kv_out, act);
+    return run_scan<false>(Q, K, V, O, lams, p, B, H, n, d, dt, (float *)workspace, s, kv_in, kv_out, var);
 }
 
 // ... and by the backward entry points.
 int backward(const void *Q, const void *K, const void *V, const float *lambda, const void *dO,
              void *dQ, void *dK, void *dV, int B, int H, int n, int d, la_dtype dt,
-             void *workspace, size_t workspace_bytes, void *hip_stream, bool swish)
+             void *workspace, size_t workspace_bytes, void *hip_stream, const Variant &var)
 {
     int rc = check_common(B, H, n, d, dt);
     if (rc != LA_OK) return rc;
@@ -411,7 +440,16 @@ int backward(const void *Q, const void *K, const void *V, const float *lambda, c
     rc = check_workspace(p, B, H, d, workspace, workspace_bytes, true);
     if (rc != LA_OK) return rc;
     return run_backward(Q, K, V, dO, dQ, dK, dV, lams, p, B, H, n, d, dt, (float *)workspace,
-                        (hipStream_t)hip_stream, swish);
+                        (hipStream_t)hip_stream, var);
+}
+
+// d_k = m * d_v: the scores add over the m slices of the query / key features, so the
+// attention is the sum of m ordinary ones (App. A's kv state becomes m d_v x d_v states).
+int check_wide(int dk, int dv)
+{
+    if (dv != 64 && dv != 128) return LA_ERR_SHAPE;
+    if (dk < dv || dk % dv != 0 || dk / dv > 4) return LA_ERR_SHAPE;
+    return LA_OK;
 }
 
 }  // namespace
@@ -442,7 +480,7 @@ int la_fwd_state(const void *Q, const void *K, const void *V, const float *lambd
                  void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     return forward(Q, K, V, lambda, O, kv_in, kv_out, B, H, n, d, dt, workspace, workspace_bytes,
-                   hip_stream, 0);
+                   hip_stream, Variant());
 }
 
 int la_fwd(const void *Q, const void *K, const void *V, const float *lambda, void *O,
@@ -450,7 +488,7 @@ int la_fwd(const void *Q, const void *K, const void *V, const float *lambda, voi
            void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     return forward(Q, K, V, lambda, O, nullptr, nullptr, B, H, n, d, dt, workspace, workspace_bytes,
-                   hip_stream, 0);
+                   hip_stream, Variant());
 }
 
 int la_fwd_swish(const void *Qp, const void *Kp, const void *V, const float *lambda, void *O,
@@ -458,8 +496,30 @@ int la_fwd_swish(const void *Qp, const void *Kp, const void *V, const float *lam
                  void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     // O = scan(phi(Qp), phi(Kp), V)
+    Variant var;
+    var.swish = true;
     return forward(Qp, Kp, V, lambda, O, nullptr, nullptr, B, H, n, d, dt, workspace, workspace_bytes,
-                   hip_stream, LA_ACT_A | LA_ACT_BM);
+                   hip_stream, var);
+}
+
+int la_fwd_wide(const void *Qw, const void *Kw, const void *V, const float *lambda, void *O,
+                int B, int H, int n, int dk, int dv, la_dtype dt,
+                void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_common(B, H, n, dv, dt);
+    if (rc == LA_OK) rc = check_wide(dk, dv);
+    if (rc != LA_OK) return rc;
+    if (!Qw || !Kw) return LA_ERR_NULL;
+    const size_t esz = dt == LA_BF16 ? 2 : 4;
+    for (int j = 0; j < dk / dv; ++j) {
+        Variant var;
+        var.wide_ld = dk;
+        var.accumulate = j > 0;
+        rc = forward((const char *)Qw + (size_t)j * dv * esz, (const char *)Kw + (size_t)j * dv * esz, V,
+                     lambda, O, nullptr, nullptr, B, H, n, dv, dt, workspace, workspace_bytes, hip_stream, var);
+        if (rc != LA_OK) return rc;
+    }
+    return LA_OK;
 }
 
 int la_decode_step(const void *q, const void *k, const void *v, const float *lambda,
@@ -491,7 +551,7 @@ int la_bwd(const void *Q, const void *K, const void *V, const float *lambda, con
            void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     return backward(Q, K, V, lambda, dO, dQ, dK, dV, B, H, n, d, dt, workspace, workspace_bytes,
-                    hip_stream, false);
+                    hip_stream, Variant());
 }
 
 int la_bwd_swish(const void *Qp, const void *Kp, const void *V, const float *lambda, const void *dO,
@@ -499,8 +559,32 @@ int la_bwd_swish(const void *Qp, const void *Kp, const void *V, const float *lam
                  int B, int H, int n, int d, la_dtype dt,
                  void *workspace, size_t workspace_bytes, void *hip_stream)
 {
+    Variant var;
+    var.swish = true;
     return backward(Qp, Kp, V, lambda, dO, dQp, dKp, dV, B, H, n, d, dt, workspace, workspace_bytes,
-                    hip_stream, true);
+                    hip_stream, var);
+}
+
+int la_bwd_wide(const void *Qw, const void *Kw, const void *V, const float *lambda, const void *dO,
+                void *dQw, void *dKw, void *dV,
+                int B, int H, int n, int dk, int dv, la_dtype dt,
+                void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_common(B, H, n, dv, dt);
+    if (rc == LA_OK) rc = check_wide(dk, dv);
+    if (rc != LA_OK) return rc;
+    if (!Qw || !Kw || !dQw || !dKw) return LA_ERR_NULL;
+    const size_t esz = dt == LA_BF16 ? 2 : 4;
+    for (int j = 0; j < dk / dv; ++j) {
+        Variant var;
+        var.wide_ld = dk;
+        var.accumulate = j > 0;
+        const size_t off = (size_t)j * dv * esz;
+        rc = backward((const char *)Qw + off, (const char *)Kw + off, V, lambda, dO, (char *)dQw + off,
+                      (char *)dKw + off, dV, B, H, n, dv, dt, workspace, workspace_bytes, hip_stream, var);
+        if (rc != LA_OK) return rc;
+    }
+    return LA_OK;
 }
 
 int la_gate_norm_fwd(const void *O, const void *U, void *Y, float eps,

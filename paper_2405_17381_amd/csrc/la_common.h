@@ -41,6 +41,15 @@ struct LaLambdas {
                                 // slowly decaying heads (longest chains) first
 };
 
+// Where one (batch, head) slab of an operand lives: element offset b * bs + h * hs, rows
+// `ld` elements apart.  Contiguous [B, H, n, D]: bs = H n D, hs = n D, ld = D.  A slice of
+// D features out of a wider tensor has the wider row as ld.  Only the kernel variants built
+// with the extensions (ACT) read these; the plain ones assume the contiguous layout.
+struct LaLayout {
+    long bs, hs;
+    int ld;
+};
+
 struct ScanArgs {
     const void *A;       // role of Q   [scans, n, D]
     const void *Bm;      // role of K
@@ -64,13 +73,17 @@ struct ScanArgs {
     int act;             // LA_ACT_* bits: operands that are pre-activations (Swish is applied
                          // as they are staged) and whether Out is a pre-activation gradient
     const void *E;       // LA_ACT_OUT: the pre-activation whose gradient Out is, [scans, n, D]
+    LaLayout lA, lB, lC, lO, lE;   // layouts of A, Bm, C, Out, E
 };
 
 // Swish on the query / key projections (Sec. 4.2: Q = phi(X W_q), K = phi(X W_k)).
 // The scans take the pre-activations and apply phi while staging a tile; a scan
 // whose result is the gradient of an activated operand multiplies it by phi' of the
 // matching pre-activation tile as it is stored (chain rule).
-enum : int { LA_ACT_A = 1, LA_ACT_BM = 2, LA_ACT_C = 4, LA_ACT_OUT = 8 };
+// LA_ACT_ACC: the result is added to what Out already holds (a scan over one slice of a
+// wider query / key feature dimension adds to the scans over the other slices).
+// LA_ACT_EXT alone only selects the extended kernel variants (strided operands).
+enum : int { LA_ACT_A = 1, LA_ACT_BM = 2, LA_ACT_C = 4, LA_ACT_OUT = 8, LA_ACT_ACC = 16, LA_ACT_EXT = 32 };
 
 // phi(x) = x sigmoid(x).  exp2 overflows to +inf for x < -88, giving sigmoid = 0: the limit.
 __device__ __forceinline__ float la_sigmoid(float x)

@@ -94,6 +94,16 @@ __device__ __forceinline__ U4 mul_swish_grad_u4(U4 r, U4 x)
     return o;
 }
 
+// sum of two chunks of 8 bf16 (fp32 add, one rounding)
+__device__ __forceinline__ U4 add_u4(U4 r, U4 x)
+{
+    U4 o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        o[j] = pack2_bf16(bf16_lo(r[j]) + bf16_lo(x[j]), bf16_hi(r[j]) + bf16_hi(x[j]));
+    return o;
+}
+
 template <int D>
 struct Bf16Cfg {
     static constexpr int BK = 64;
@@ -148,14 +158,23 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
     const int seg_hi = min(a.n, seg_lo + a.L);
     const int nblk = (seg_hi - seg_lo + BK - 1) / BK;
 
-    const size_t base = (size_t)scan * a.n * D;
-    const uint16_t *gA = (const uint16_t *)a.A + base;
-    const uint16_t *gB = (const uint16_t *)a.Bm + base;
-    const uint16_t *gC = (const uint16_t *)a.C + base;
-    uint16_t *gO = (uint16_t *)a.Out + base;
     const int act = ACT ? a.act : 0;
-    const uint16_t *gE = (ACT && (act & LA_ACT_OUT)) ? (const uint16_t *)a.E + base : gA;
-
+    // operand slabs: contiguous [scans, n, D] in the plain variants, free layouts otherwise
+    const size_t base = (size_t)scan * a.n * D;
+    const int bi = scan / a.H, hi = scan % a.H;
+    auto slab = [&](const void *p, const LaLayout &l) -> uint16_t * {
+        return (uint16_t *)p + (ACT ? (size_t)bi * l.bs + (size_t)hi * l.hs : base);
+    };
+    const uint16_t *gA = slab(a.A, a.lA);
+    const uint16_t *gB = slab(a.Bm, a.lB);
+    const uint16_t *gC = slab(a.C, a.lC);
+    uint16_t *gO = slab(a.Out, a.lO);
+    const int ldA = ACT ? a.lA.ld : D, ldB = ACT ? a.lB.ld : D, ldC = ACT ? a.lC.ld : D;
+    const int ldO = ACT ? a.lO.ld : D;
+    // tile fetched for the epilogue: the pre-activation (phi') or the previous Out (accumulate)
+    const bool epi_e = ACT && (act & LA_ACT_OUT), epi_acc = ACT && (act & LA_ACT_ACC);
+    const uint16_t *gE = epi_e ? slab(a.E, a.lE) : gO;
+    const int ldE = epi_e ? a.lE.ld : ldO;
     // ---- per-lane constants --------------------------------------------------
     float wst[4];                              // state-update weight of staged rows
 #pragma unroll
@@ -253,16 +272,20 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int t = t0 + 4 * sa + i;
-            const size_t off = (size_t)min(t, seg_hi - 1) * D + 8 * sc;
+            const size_t row = (size_t)min(t, seg_hi - 1);
+            const size_t off = row * D + 8 * sc;         // plain variants: one offset for all
+            const U4 *pa = (const U4 *)(ACT ? gA + row * ldA + 8 * sc : gA + off);
+            const U4 *pb = (const U4 *)(ACT ? gB + row * ldB + 8 * sc : gB + off);
+            const U4 *pc = (const U4 *)(ACT ? gC + row * ldC + 8 * sc : gC + off);
             if (nt_all) {
-                rb[i] = __builtin_nontemporal_load((const U4 *)(gB + off));
-                rc[i] = __builtin_nontemporal_load((const U4 *)(gC + off));
+                rb[i] = __builtin_nontemporal_load(pb);
+                rc[i] = __builtin_nontemporal_load(pc);
             } else {
-                rb[i] = *(const U4 *)(gB + off);
-                rc[i] = *(const U4 *)(gC + off);
+                rb[i] = *pb;
+                rc[i] = *pc;
             }
-            if (nt_a) ra[i] = __builtin_nontemporal_load((const U4 *)(gA + off));
-            else ra[i] = *(const U4 *)(gA + off);
+            if (nt_a) ra[i] = __builtin_nontemporal_load(pa);
+            else ra[i] = *pa;
         }
     };
     // ---- registers -> LDS, transposing C and the weighted Bm ---------------------
@@ -466,11 +489,11 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
         // Epilogue operand: the pre-activation tile whose phi' scales Out.  Loaded here, where
         // the Out accumulators have just died, and used after the state update.
         U4 re[4];
-        if (ACT && (act & LA_ACT_OUT)) {
+        if (epi_e || epi_acc) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
             {
-                const U4 *pe = (const U4 *)(gE + (size_t)min(t0 + 4 * sa + i, seg_hi - 1) * D + 8 * sc);
+                const U4 *pe = (const U4 *)(gE + (size_t)min(t0 + 4 * sa + i, seg_hi - 1) * ldE + 8 * sc);
                 re[i] = nt_all ? __builtin_nontemporal_load(pe) : *pe;
             }
         }
@@ -499,8 +522,9 @@ __global__ __launch_bounds__(D * 2, 2) void la_scan_bf16(ScanLaunch launch, LaLa
                 U2 lo = *(const U2 *)(po);
                 U2 hi = *(const U2 *)(po + 8);
                 U4 out = {lo[0], lo[1], hi[0], hi[1]};
-                if (ACT && (act & LA_ACT_OUT)) out = mul_swish_grad_u4(out, re[i]);
-                if (t < seg_hi) __builtin_nontemporal_store(out, (U4 *)(gO + (size_t)t * D + 8 * sc));
+                if (epi_e) out = mul_swish_grad_u4(out, re[i]);
+                else if (epi_acc) out = add_u4(out, re[i]);
+                if (t < seg_hi) __builtin_nontemporal_store(out, (U4 *)(gO + (size_t)t * ldO + 8 * sc));
             }
         }
     }

@@ -53,11 +53,14 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
     }
     const int nblk = (seg_hi - seg_lo + BK - 1) / BK;
 
-    const float *gA = (const float *)a.A + (size_t)scan * a.n * D;
-    const float *gB = (const float *)a.Bm + (size_t)scan * a.n * D;
-    const float *gC = (const float *)a.C + (size_t)scan * a.n * D;
-    float *gO = (float *)a.Out + (size_t)scan * a.n * D;
-    const float *gE = (a.act & LA_ACT_OUT) ? (const float *)a.E + (size_t)scan * a.n * D : gA;
+    // operand slabs (layouts are filled in for every launch; contiguous by default)
+    const int bi = scan / a.H, hi = scan % a.H;
+    const float *gA = (const float *)a.A + (size_t)bi * a.lA.bs + (size_t)hi * a.lA.hs;
+    const float *gB = (const float *)a.Bm + (size_t)bi * a.lB.bs + (size_t)hi * a.lB.hs;
+    const float *gC = (const float *)a.C + (size_t)bi * a.lC.bs + (size_t)hi * a.lC.hs;
+    float *gO = (float *)a.Out + (size_t)bi * a.lO.bs + (size_t)hi * a.lO.hs;
+    const float *gE = (a.act & LA_ACT_OUT) ? (const float *)a.E + (size_t)bi * a.lE.bs + (size_t)hi * a.lE.hs : gA;
+    const int ldA = a.lA.ld, ldB = a.lB.ld, ldC = a.lC.ld, ldO = a.lO.ld, ldE = a.lE.ld;
     float *gSt = a.states ? a.states + ((size_t)scan * a.S + seg) * (size_t)(D * D) : nullptr;
 
     // lambda^k, k = 0..BK, evaluated in double then rounded once
@@ -87,9 +90,9 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
             int t = t0 + r;
             float4 vb = make_float4(0.f, 0.f, 0.f, 0.f), vc = vb, va = vb;
             if (t < seg_hi) {
-                vb = *(const float4 *)(gB + (size_t)t * D + c4);
-                vc = *(const float4 *)(gC + (size_t)t * D + c4);
-                if (!STATE_ONLY) va = *(const float4 *)(gA + (size_t)t * D + c4);
+                vb = *(const float4 *)(gB + (size_t)t * ldB + c4);
+                vc = *(const float4 *)(gC + (size_t)t * ldC + c4);
+                if (!STATE_ONLY) va = *(const float4 *)(gA + (size_t)t * ldA + c4);
                 // Swish prologue on the operands that are pre-activations
                 if (a.act & LA_ACT_BM) vb = make_float4(la_swish(vb.x), la_swish(vb.y), la_swish(vb.z), la_swish(vb.w));
                 if (a.act & LA_ACT_C) vc = make_float4(la_swish(vc.x), la_swish(vc.y), la_swish(vc.z), la_swish(vc.w));
@@ -171,8 +174,9 @@ __global__ __launch_bounds__(256) void la_scan_f32(ScanLaunch launch, LaLambdas 
                     for (int j = 0; j < CJ; ++j)
                     {
                         float o = fmaf(rs, ox[i][j], oi[i][j]);
-                        if (a.act & LA_ACT_OUT) o *= la_swish_grad(gE[(size_t)t * D + tx + 16 * j]);
-                        gO[(size_t)t * D + tx + 16 * j] = o;
+                        if (a.act & LA_ACT_OUT) o *= la_swish_grad(gE[(size_t)t * ldE + tx + 16 * j]);
+                        if (a.act & LA_ACT_ACC) o += gO[(size_t)t * ldO + tx + 16 * j];
+                        gO[(size_t)t * ldO + tx + 16 * j] = o;
                     }
                 }
             }

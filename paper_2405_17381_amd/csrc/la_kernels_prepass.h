@@ -61,8 +61,10 @@ __global__ __launch_bounds__(D * 2, 2) void la_prepass_bf16(ScanLaunch launch, L
     }
 
     const size_t base = (size_t)scan * a.n * D;
-    const uint16_t *gB = (const uint16_t *)a.Bm + base;
-    const uint16_t *gC = (const uint16_t *)a.C + base;
+    const int bi = scan / a.H, hi = scan % a.H;
+    const uint16_t *gB = (const uint16_t *)a.Bm + (ACT ? (size_t)bi * a.lB.bs + (size_t)hi * a.lB.hs : base);
+    const uint16_t *gC = (const uint16_t *)a.C + (ACT ? (size_t)bi * a.lC.bs + (size_t)hi * a.lC.hs : base);
+    const int ldB = ACT ? a.lB.ld : D, ldC = ACT ? a.lC.ld : D;
     float *gSt = a.states + ((size_t)scan * a.S + seg) * (size_t)(D * D);
 
     float wrow[4];                                           // weight of staged rows inside a block
@@ -89,9 +91,10 @@ __global__ __launch_bounds__(D * 2, 2) void la_prepass_bf16(ScanLaunch launch, L
         const int t0 = seg_lo + blk_of(ib) * BK;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const size_t off = (size_t)min(t0 + 4 * sa + i, seg_hi - 1) * D + 8 * sc;
-            rb_all[slot][i] = __builtin_nontemporal_load((const U4 *)(gB + off));
-            rc_all[slot][i] = __builtin_nontemporal_load((const U4 *)(gC + off));
+            const size_t row = (size_t)min(t0 + 4 * sa + i, seg_hi - 1);
+            const size_t off = row * D + 8 * sc;             // plain variant: one offset for both
+            rb_all[slot][i] = __builtin_nontemporal_load((const U4 *)(ACT ? gB + row * ldB + 8 * sc : gB + off));
+            rc_all[slot][i] = __builtin_nontemporal_load((const U4 *)(ACT ? gC + row * ldC + 8 * sc : gC + off));
         }
     };
 

@@ -1,0 +1,111 @@
+"""GPU parity of the attention with a query / key feature wider than the value feature
+(la_fwd_wide, la_bwd_wide), and of LRPE-d served through it, against the CPU oracle."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2405_17381_amd import binding
+
+pytestmark = pytest.mark.gpu
+TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def _draw(B, H, n, dk, dv, dtype, seed):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    Qw = torch.randn((B, H, n, dk), generator=g) / dk ** 0.5
+    Kw = torch.randn((B, H, n, dk), generator=g) / dk ** 0.5
+    V = torch.randn((B, H, n, dv), generator=g) / dv ** 0.5
+    dO = torch.randn((B, H, n, dv), generator=g)
+    return [x.to(TDT[dtype]) for x in (Qw, Kw, V, dO)]
+
+
+def _run(xs, lam, lseg):
+    if lseg is not None:
+        os.environ["LA_LSEG"] = str(lseg)
+    try:
+        Qw, Kw, V, dO = [x.cuda() for x in xs]
+        O = binding.la_fwd_wide(Qw, Kw, V, lam)
+        dQw, dKw, dV = binding.la_bwd_wide(Qw, Kw, V, lam, dO)
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("LA_LSEG", None)
+    return [t.to(torch.float64).cpu().numpy() for t in (O, dQw, dKw, dV)]
+
+
+def _reference(xs, lam):
+    """The compiled recurrence handles square states: use the slice-sum identity the oracle's
+    pins establish (scores add over the slices of d_v features)."""
+    qw, kw, v, g = [x.to(torch.float64).numpy() for x in xs]
+    dv = v.shape[3]
+    m = qw.shape[3] // dv
+    O = np.zeros_like(v)
+    dQw, dKw, dV = np.empty_like(qw), np.empty_like(kw), np.zeros_like(v)
+    for j in range(m):
+        sl = slice(j * dv, (j + 1) * dv)
+        q, k = np.ascontiguousarray(qw[..., sl]), np.ascontiguousarray(kw[..., sl])
+        O += oracle.c_recurrence_fwd(q, k, v, lam)
+        a, b, c = oracle.c_recurrence_bwd(q, k, v, lam, g)
+        dQw[..., sl], dKw[..., sl] = a, b
+        dV += c
+    return O, dQw, dKw, dV
+
+
+@pytest.mark.parametrize("dtype,B,H,n,dk,dv,lseg", [
+    ("f32", 1, 2, 300, 128, 64, None), ("f32", 2, 2, 200, 128, 64, 64), ("f32", 1, 2, 150, 256, 128, None),
+    ("bf16", 2, 4, 1000, 256, 128, None), ("bf16", 2, 4, 1000, 256, 128, 256), ("bf16", 1, 3, 1, 256, 128, None),
+    ("bf16", 2, 3, 700, 128, 64, None), ("bf16", 2, 3, 700, 192, 64, 192), ("bf16", 1, 2, 333, 128, 128, None),
+    ("bf16", 1, 16, 4096, 256, 128, 1024),
+])
+def test_wide_attention_against_oracle(dtype, B, H, n, dk, dv, lseg):
+    assert torch.cuda.is_available()
+    lam = [1.0, 0.999, 0.97, 0.9][:H] if H <= 4 else list(np.linspace(0.9, 1.0, H))
+    xs = _draw(B, H, n, dk, dv, dtype, seed=6000 + n + dk)
+    got = _run(xs, lam, lseg)
+    ref = _reference(xs, lam)
+    for nm, x, r in zip(("O", "dQw", "dKw", "dV"), got, ref):
+        assert np.all(np.isfinite(x)), nm
+        err = oracle.rel_max_err(x, r)
+        assert err <= TOL[dtype], (nm, err)
+
+
+def test_small_case_against_the_quadratic_form():
+    """No slice-sum identity in the reference: the oracle's quadratic form takes the wide operands as they are."""
+    lam = [0.9, 1.0]
+    xs = _draw(1, 2, 96, 128, 64, "f32", seed=61)
+    got = _run(xs, lam, None)
+    qw, kw, v, g = [x.to(torch.float64).numpy() for x in xs]
+    ref = (oracle.left_product_fwd(qw, kw, v, lam),) + oracle.left_product_bwd(qw, kw, v, lam, g)
+    for nm, x, r in zip(("O", "dQw", "dKw", "dV"), got, ref):
+        assert oracle.rel_max_err(x, r) <= 1e-4, nm
+
+
+def test_lrpe_d_through_the_wide_entry_point():
+    """LRPE-d: rotate q and k into cos / sin features (here on the host, in fp64), run the wide
+    attention on the GPU, compare with the definition written out term by term."""
+    B, H, n, d = 1, 2, 80, 64
+    lam = [0.95, 1.0]
+    rng = np.random.default_rng(5)
+    theta = rng.uniform(0.0, 1.0, size=(H, d))
+    Q, K, V = (rng.standard_normal((B, H, n, d)) / d ** 0.5 for _ in range(3))
+    Qw = torch.from_numpy(oracle.lrpe_features(Q, theta)).float().cuda()
+    Kw = torch.from_numpy(oracle.lrpe_features(K, theta)).float().cuda()
+    O = binding.la_fwd_wide(Qw, Kw, torch.from_numpy(V).float().cuda(), lam)
+    torch.cuda.synchronize()
+    ref = oracle.lrpe_fwd(Q, K, V, lam, theta)
+    assert oracle.rel_max_err(O.double().cpu().numpy(), ref) <= 1e-4
+
+
+def test_dk_equal_dv_is_the_plain_attention_bit_for_bit():
+    lam = [0.99, 0.9]
+    xs = _draw(2, 2, 500, 128, 128, "bf16", seed=62)
+    wide = _run(xs, lam, None)
+    Q, K, V, dO = [x.cuda() for x in xs]
+    O = binding.la_fwd(Q, K, V, lam)
+    dQ, dK, dV = binding.la_bwd(Q, K, V, lam, dO)
+    torch.cuda.synchronize()
+    for a, b in zip(wide, (O, dQ, dK, dV)):
+        assert np.array_equal(a, b.double().cpu().numpy())
