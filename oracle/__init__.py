@@ -18,7 +18,7 @@ import subprocess
 import numpy as np
 
 from .la_oracle import (decay_matrix, decode_step, gate_norm_bwd, gate_norm_fwd, left_product_bwd,
-                        left_product_fwd, lrpe_features, lrpe_fwd, recurrence_bwd, recurrence_fwd, rel_max_err, swish,
+                        left_product_fwd, lrpe_features, lrpe_features_bwd, lrpe_fwd, recurrence_bwd, recurrence_fwd, rel_max_err, swish,
                         swish_attention_bwd, swish_attention_fwd, swish_grad)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

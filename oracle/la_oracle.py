@@ -247,3 +247,18 @@ def lrpe_features(X, theta):
     B, H, n, d = X.shape
     ang = np.arange(n, dtype=np.float64)[None, :, None] * theta[:, None, :]      # [H, n, d]
     return np.concatenate([X * np.cos(ang)[None], X * np.sin(ang)[None]], axis=3)
+
+
+def lrpe_features_bwd(X, theta, dXw):
+    """Gradients of Xw = lrpe_features(X, theta) given dXw ([B, H, n, 2d]):
+    dX = dXw_c cos(t theta) + dXw_s sin(t theta);
+    dtheta[h, i] = sum_{b, t} t x_ti (dXw_s cos(t theta_i) - dXw_c sin(t theta_i))."""
+    X, theta, dXw = _as64(X), _as64(theta), _as64(dXw)
+    B, H, n, d = X.shape
+    t = np.arange(n, dtype=np.float64)[None, :, None]
+    ang = t * theta[:, None, :]                                   # [H, n, d]
+    c, s = np.cos(ang)[None], np.sin(ang)[None]
+    gc, gs = dXw[..., :d], dXw[..., d:]
+    dX = gc * c + gs * s
+    dtheta = np.sum(t[None] * X * (gs * c - gc * s), axis=(0, 2))
+    return dX, dtheta

@@ -456,3 +456,30 @@ def test_lrpe_definition_equals_attention_over_rotated_features():
     full = oracle.lrpe_fwd(Q, K0, V0, lam, theta)
     cut = oracle.lrpe_fwd(Q[:, :, 1:], K0[:, :, 1:], V0[:, :, 1:], lam, theta)
     np.testing.assert_allclose(full[:, :, 1:], cut, rtol=1e-12, atol=1e-13)
+
+
+def test_lrpe_feature_gradients_by_finite_differences():
+    rng = np.random.default_rng(23)
+    B, H, n, d = 2, 2, 6, 3
+    theta = rng.uniform(0.0, 2.0, size=(H, d))
+    X = rng.standard_normal((B, H, n, d))
+    G = rng.standard_normal((B, H, n, 2 * d))
+    dX, dtheta = oracle.lrpe_features_bwd(X, theta, G)
+    loss = lambda x, th: float(np.sum(G * oracle.lrpe_features(x, th)))
+    h = 1e-6
+    for idx in np.ndindex(X.shape):
+        a, b = X.copy(), X.copy()
+        a[idx] += h
+        b[idx] -= h
+        assert abs((loss(a, theta) - loss(b, theta)) / (2 * h) - dX[idx]) <= 1e-8 * max(1.0, abs(dX[idx]))
+    for idx in np.ndindex(theta.shape):
+        a, b = theta.copy(), theta.copy()
+        a[idx] += h
+        b[idx] -= h
+        assert abs((loss(X, a) - loss(X, b)) / (2 * h) - dtheta[idx]) <= 1e-7 * max(1.0, abs(dtheta[idx]))
+    # rotation keeps the norm of every row pair: |Xw|^2 = |X|^2
+    Xw = oracle.lrpe_features(X, theta)
+    np.testing.assert_allclose(np.sum(Xw * Xw, axis=3), np.sum(X * X, axis=3), rtol=1e-12)
+    # row 0 is not rotated
+    np.testing.assert_allclose(Xw[:, :, 0, :d], X[:, :, 0])
+    np.testing.assert_allclose(Xw[:, :, 0, d:], 0.0, atol=0)
