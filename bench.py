@@ -264,6 +264,34 @@ def main():
                            "tiles of the phi' epilogue are extra reads); separate activation kernels would "
                            "add 10 passes to the plain path's 14"}
 
+    # ---- LRPE-d layer (next row): rotation + attention over 2d-wide query / key features ----------
+    lB, ln = 1, TOKENS
+    t = views(lB, ln)
+    theta = torch.rand((H, D), device=dev, dtype=torch.float32)
+    qw = torch.empty((lB, H, ln, 2 * D), device=dev, dtype=torch.bfloat16)
+    kw = torch.empty_like(qw)
+    dqw = torch.empty_like(qw)
+    dkw = torch.empty_like(qw)
+    dth = torch.zeros((H, D), device=dev, dtype=torch.float32)
+    lws = torch.empty(max(256, binding.la_lrpe_workspace_bytes(lB, H, ln, D)), dtype=torch.uint8, device=dev)
+    rot_f = _time(lambda: binding.la_lrpe_rotate_fwd(t["Q"], theta, Xw=qw))
+    binding.la_lrpe_rotate_fwd(t["K"], theta, Xw=kw)
+    rot_b = _time(lambda: binding.la_lrpe_rotate_bwd(t["Q"], theta, dqw, dX=t["dQ"], dtheta=dth, workspace=lws))
+    wf = _time(lambda: binding.la_fwd_wide(qw, kw, t["V"], lam, O=t["O"], workspace=ws))
+    wb = _time(lambda: binding.la_bwd_wide(qw, kw, t["V"], lam, t["dO"], dQw=dqw, dKw=dkw, dV=t["dV"], workspace=ws))
+    layer_ms = 2 * rot_f + wf + wb + 2 * rot_b
+    lrpe = {"workload": "LRPE-d attention layer, [1,16,65536,128] bf16: rotate Q and K (2d-wide features), "
+                        "la_fwd_wide, la_bwd_wide, rotation backward for Q and K (with the theta gradient)",
+            "rotate_fwd_ms": round(rot_f, 4), "rotate_bwd_ms": round(rot_b, 4),
+            "rotate_fwd_GBps": round(3 * tensor_bytes / (rot_f * 1e-3) / 1e9, 1),
+            "rotate_bwd_GBps": round(4 * tensor_bytes / (rot_b * 1e-3) / 1e9, 1),
+            "wide_fwd_ms": round(wf, 4), "wide_bwd_ms": round(wb, 4),
+            "layer_fwd_bwd_ms": round(layer_ms, 4),
+            "tokens_per_s": round(TOKENS / (layer_ms * 1e-3), 1),
+            "note": "wide attention = two accumulated scans over the cos and the sin half (twice the plain "
+                    "path's traffic plus the accumulator re-reads); rotation: 1 tensor in, 2 out (forward), "
+                    "3 in, 1 out (backward)"}
+
     total_tflops = value * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12
     out = {
         "metric": "fwd+bwd tokens/s (causal linear attention with decay, bf16, d=128, seq-len sweep "
@@ -283,6 +311,7 @@ def main():
         "decode": decode,
         "gate_norm": gate_norm,
         "swish_fused": swish_fused,
+        "lrpe_d": lrpe,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()

@@ -204,6 +204,29 @@ int la_bwd_wide(const void *Qw, const void *Kw, const void *V,
                 int B, int H, int n, int dk, int dv, la_dtype dt,
                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * LRPE-d rotation (Sec. 4.1, "Position Encoding"; the decomposition of
+ * exp(i theta (t - s)) over t and s): for row t (counted from 0) of every (batch, head),
+ *     Xw[t] = [ X[t] * cos(t theta_h) , X[t] * sin(t theta_h) ]        ([B, H, n, 2d])
+ * with theta a DEVICE pointer to [H, d] fp32 angles in radians (one per head and
+ * feature; it is a learnable parameter of the model, so it lives on the device).
+ * la_fwd_wide / la_bwd_wide on the rotated Q and K give LRPE-d's attention.
+ * Backward:  dX[t] = dXw_c[t] cos(t theta) + dXw_s[t] sin(t theta)  and
+ *     dtheta[h, i] (+)= sum_{b, t} t X[t, i] (dXw_s[t, i] cos(t theta_i) - dXw_c[t, i] sin(t theta_i)),
+ * dtheta: DEVICE [H, d] fp32, overwritten, or added to when accumulate_dtheta != 0
+ * (query and key share theta: rotate both, accumulate the second call).  The
+ * reduction uses no atomics: `workspace` (DEVICE, 256-byte aligned, at least
+ * la_lrpe_workspace_bytes(...) bytes, contents scratch) holds per-tile partial sums
+ * that a second kernel adds in a fixed order.  B * H <= 65535.
+ */
+size_t la_lrpe_workspace_bytes(int B, int H, int n, int d);
+int la_lrpe_rotate_fwd(const void *X, const float *theta /* device, [H, d] */, void *Xw,
+                       int B, int H, int n, int d, la_dtype dt, void *hip_stream);
+int la_lrpe_rotate_bwd(const void *X, const float *theta /* device, [H, d] */, const void *dXw,
+                       void *dX, float *dtheta /* device, [H, d] */, int accumulate_dtheta,
+                       void *workspace, size_t workspace_bytes,
+                       int B, int H, int n, int d, la_dtype dt, void *hip_stream);
+
 /* Static, human-readable text for an la_status value. */
 const char *la_strerror(int status);
 

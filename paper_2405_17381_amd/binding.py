@@ -16,8 +16,8 @@ LA_F32, LA_BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libla.so")
 EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_fwd_state", "la_decode_step", "la_gate_norm_fwd",
-           "la_gate_norm_bwd", "la_fwd_swish", "la_bwd_swish", "la_fwd_wide", "la_bwd_wide", "la_strerror",
-           "la_plan",
+           "la_gate_norm_bwd", "la_fwd_swish", "la_bwd_swish", "la_fwd_wide", "la_bwd_wide", "la_lrpe_workspace_bytes",
+           "la_lrpe_rotate_fwd", "la_lrpe_rotate_bwd", "la_strerror", "la_plan",
            "la_profile_enable", "la_profile_collect")
 _lib = None
 
@@ -52,6 +52,12 @@ def load_library():
     lib.la_fwd_wide.restype = ci
     lib.la_bwd_wide.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.la_bwd_wide.restype = ci
+    lib.la_lrpe_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.la_lrpe_workspace_bytes.restype = sz
+    lib.la_lrpe_rotate_fwd.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
+    lib.la_lrpe_rotate_fwd.restype = ci
+    lib.la_lrpe_rotate_bwd.argtypes = [vp, vp, vp, vp, vp, ci, vp, sz, ci, ci, ci, ci, ci, vp]
+    lib.la_lrpe_rotate_bwd.restype = ci
     lib.la_fwd_state.argtypes = [vp, vp, vp, fp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.la_fwd_state.restype = ci
     lib.la_decode_step.argtypes = [vp, vp, vp, fp, vp, vp, ci, ci, ci, ci, vp]
@@ -273,6 +279,60 @@ def la_bwd_wide(Qw, Kw, V, lam, dO, dQw=None, dKw=None, dV=None, workspace: Opti
     if rc != 0:
         raise LaError(rc, "la_bwd_wide")
     return dQw, dKw, dV
+
+
+def _check_theta(theta, H, d, device):
+    if (not theta.is_cuda or theta.device != device or theta.dtype != torch.float32
+            or tuple(theta.shape) != (H, d) or not theta.is_contiguous()):
+        raise ValueError("la: theta must be a contiguous float32 [H, d] tensor on the tensors' device")
+
+
+def la_lrpe_workspace_bytes(B: int, H: int, n: int, d: int) -> int:
+    return int(load_library().la_lrpe_workspace_bytes(B, H, n, d))
+
+
+def la_lrpe_rotate_fwd(X, theta, Xw=None):
+    """Xw = [X cos(t theta), X sin(t theta)] ([B, H, n, 2d]); theta: float32 [H, d] on the device."""
+    _check([X])
+    B, H, n, d = X.shape
+    _check_theta(theta, H, d, X.device)
+    if Xw is None:
+        Xw = torch.empty((B, H, n, 2 * d), dtype=X.dtype, device=X.device)
+    _check([Xw])
+    with torch.cuda.device(X.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_lrpe_rotate_fwd(X.data_ptr(), theta.data_ptr(), Xw.data_ptr(), B, H, n, d, _dt(X), stream)
+    if rc != 0:
+        raise LaError(rc, "la_lrpe_rotate_fwd")
+    return Xw
+
+
+def la_lrpe_rotate_bwd(X, theta, dXw, dX=None, dtheta=None, accumulate: bool = False,
+                       workspace: Optional[torch.Tensor] = None):
+    """(dX, dtheta) of la_lrpe_rotate_fwd; with `accumulate` the theta gradient is added to `dtheta`."""
+    _check([X])
+    _check([dXw])
+    B, H, n, d = X.shape
+    _check_theta(theta, H, d, X.device)
+    dX = torch.empty_like(X) if dX is None else dX
+    _check([X, dX])
+    if dtheta is None:
+        if accumulate:
+            raise ValueError("la: accumulate needs an existing dtheta")
+        dtheta = torch.empty((H, d), dtype=torch.float32, device=X.device)
+    _check_theta(dtheta, H, d, X.device)
+    need = la_lrpe_workspace_bytes(B, H, n, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+    with torch.cuda.device(X.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_lrpe_rotate_bwd(X.data_ptr(), theta.data_ptr(), dXw.data_ptr(), dX.data_ptr(),
+                                               dtheta.data_ptr(), 1 if accumulate else 0, workspace.data_ptr(),
+                                               workspace.numel() * workspace.element_size(),
+                                               B, H, n, d, _dt(X), stream)
+    if rc != 0:
+        raise LaError(rc, "la_lrpe_rotate_bwd")
+    return dX, dtheta
 
 
 def la_gate_norm_fwd(O, U, eps: float = 0.0, Y=None):

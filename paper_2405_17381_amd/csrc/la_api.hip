@@ -11,6 +11,7 @@
 #include "la_kernels_bf16.h"
 #include "la_kernels_f32.h"
 #include "la_kernels_gate.h"
+#include "la_kernels_lrpe.h"
 #include "la_kernels_misc.h"
 #include "la_kernels_prepass.h"
 
@@ -402,6 +403,20 @@ int run_gate_norm(const GateArgs &g, int B, int n, int d, la_dtype dt, hipStream
     return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 
+template <bool BWD>
+int run_lrpe(const LrpeArgs &a, int B, int d, la_dtype dt, hipStream_t s)
+{
+    dim3 grid((unsigned)a.tiles, (unsigned)(B * a.H)), block(256);
+    if (dt == LA_BF16) {
+        if (d == 64) hipLaunchKernelGGL((la_lrpe_rotate_kernel<64, true, BWD>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((la_lrpe_rotate_kernel<128, true, BWD>), grid, block, 0, s, a);
+    } else {
+        if (d == 64) hipLaunchKernelGGL((la_lrpe_rotate_kernel<64, false, BWD>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((la_lrpe_rotate_kernel<128, false, BWD>), grid, block, 0, s, a);
+    }
+    return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+}
+
 // Argument checks and planning shared by the forward entry points.
 int forward(const void *Q, const void *K, const void *V, const float *lambda, void *O,
             const float *kv_in, float *kv_out, int B, int H, int n, int d, la_dtype dt,
@@ -616,6 +631,50 @@ int la_gate_norm_bwd(const void *O, const void *U, const void *dY, void *dO, voi
     g.O = O; g.U = U; g.dY = dY; g.Y = nullptr; g.dO = dO; g.dU = dU;
     g.H = H; g.n = n; g.eps = eps;
     return run_gate_norm<true>(g, B, n, d, dt, (hipStream_t)hip_stream);
+}
+
+size_t la_lrpe_workspace_bytes(int B, int H, int n, int d)
+{
+    if (B < 1 || H < 1 || n < 1 || (d != 64 && d != 128)) return 0;
+    const size_t tiles = ((size_t)n + LRPE_ROWS - 1) / LRPE_ROWS;
+    return (size_t)B * H * tiles * d * sizeof(float);
+}
+
+int la_lrpe_rotate_fwd(const void *X, const float *theta, void *Xw,
+                       int B, int H, int n, int d, la_dtype dt, void *hip_stream)
+{
+    int rc = check_common(B, H, n, d, dt);
+    if (rc != LA_OK) return rc;
+    if ((long)B * H > 65535) return LA_ERR_SHAPE;
+    if (!X || !theta || !Xw) return LA_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Xw) || ((uintptr_t)theta & 3u)) return LA_ERR_ALIGN;
+    LrpeArgs a;
+    a.X = X; a.theta = theta; a.Xw = Xw; a.dX = nullptr; a.partial = nullptr;
+    a.H = H; a.n = n; a.tiles = (n + LRPE_ROWS - 1) / LRPE_ROWS;
+    return run_lrpe<false>(a, B, d, dt, (hipStream_t)hip_stream);
+}
+
+int la_lrpe_rotate_bwd(const void *X, const float *theta, const void *dXw, void *dX, float *dtheta,
+                       int accumulate_dtheta, void *workspace, size_t workspace_bytes,
+                       int B, int H, int n, int d, la_dtype dt, void *hip_stream)
+{
+    int rc = check_common(B, H, n, d, dt);
+    if (rc != LA_OK) return rc;
+    if ((long)B * H > 65535) return LA_ERR_SHAPE;
+    if (!X || !theta || !dXw || !dX || !dtheta) return LA_ERR_NULL;
+    if (!aligned16(X) || !aligned16(dXw) || !aligned16(dX) || ((uintptr_t)theta & 3u) ||
+        ((uintptr_t)dtheta & 3u)) return LA_ERR_ALIGN;
+    if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < la_lrpe_workspace_bytes(B, H, n, d))
+        return LA_ERR_WORKSPACE;
+    LrpeArgs a;
+    a.X = X; a.theta = theta; a.Xw = const_cast<void *>(dXw); a.dX = dX; a.partial = (float *)workspace;
+    a.H = H; a.n = n; a.tiles = (n + LRPE_ROWS - 1) / LRPE_ROWS;
+    hipStream_t s = (hipStream_t)hip_stream;
+    rc = run_lrpe<true>(a, B, d, dt, s);
+    if (rc != LA_OK) return rc;
+    hipLaunchKernelGGL(la_lrpe_theta_reduce, dim3((unsigned)(H * d / 32)), dim3(256), 0, s,
+                       (const float *)workspace, dtheta, B, H, a.tiles, d, accumulate_dtheta ? 1 : 0);
+    return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 
 const char *la_strerror(int status)

@@ -122,3 +122,17 @@ def test_inference_and_output_stage_entry_points_reject_bad_arguments():
     assert lib.la_fwd_swish(P, P, P, lam, 0, 1, 1, 8, 64, 1, 0, 0, None) == -1
     assert lib.la_fwd_swish(P, P, P, lam, P, 1, 1, 8, 96, 1, 0, 0, None) == -2
     assert lib.la_bwd_swish(P, P, P, lam, P, P, P + 4, P, 1, 1, 8, 64, 1, 0, 0, None) == -7
+    # wide query / key feature: dk must be a multiple (1..4) of dv, dv in {64, 128}
+    assert lib.la_fwd_wide(P, P, P, lam, P, 1, 1, 8, 96, 64, 1, 0, 0, None) == -2
+    assert lib.la_fwd_wide(P, P, P, lam, P, 1, 1, 8, 640, 128, 1, 0, 0, None) == -2
+    assert lib.la_fwd_wide(P, P, P, lam, P, 1, 1, 8, 64, 32, 1, 0, 0, None) == -2
+    assert lib.la_fwd_wide(0, P, P, lam, P, 1, 1, 8, 128, 64, 1, 0, 0, None) == -1
+    assert lib.la_bwd_wide(P, P, P, lam, P, P, 0, P, 1, 1, 8, 128, 64, 1, 0, 0, None) == -1
+    # LRPE-d rotation: scratch query is host arithmetic; missing / small scratch, too many scans
+    assert lib.la_lrpe_workspace_bytes(2, 3, 300, 64) == 2 * 3 * 3 * 64 * 4
+    assert lib.la_lrpe_workspace_bytes(2, 3, 300, 96) == 0
+    assert lib.la_lrpe_rotate_fwd(P, 0, P, 1, 1, 8, 64, 1, None) == -1
+    assert lib.la_lrpe_rotate_fwd(P, P, P, 300, 300, 8, 64, 1, None) == -2
+    assert lib.la_lrpe_rotate_bwd(P, P, P, P, P, 0, 0, 0, 1, 1, 8, 64, 1, None) == -5
+    assert lib.la_lrpe_rotate_bwd(P, P, P, P, P, 0, P, 16, 1, 1, 8, 64, 1, None) == -5
+    assert lib.la_lrpe_rotate_bwd(P, P, P, P, 0, 0, P, 1 << 20, 1, 1, 8, 64, 1, None) == -1
