@@ -15,6 +15,7 @@ import math
 from dataclasses import dataclass, field
 from typing import List, Optional, Sequence, Tuple
 
+import numpy as np
 import torch
 
 BASE_SEED = 20240517
@@ -45,6 +46,11 @@ class Workload:
     seed: int
     silu_qk: bool = False           # Q, K = silu(N(0,1)) / sqrt(d)
     note: str = ""
+
+    def __post_init__(self):
+        # The C ABI takes the decay rates as float32: hold exactly those values, so that the
+        # library and the oracle are given the same numbers (like tensor values after their cast).
+        self.lambdas = [float(np.float32(x)) for x in self.lambdas]
 
     @property
     def tokens(self) -> int:
