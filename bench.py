@@ -136,32 +136,42 @@ def main():
     tokens_per_step = TOKENS * len(POINTS)
     value = tokens_per_step * args.steps / elapsed
 
-    # ---- per sweep point (events on the stream the kernels run on) -------------
+    # ---- per sweep point: 5 warm-up + 20 timed iterations of la_fwd, of la_bwd and of the two back to
+    # back, one pair of events per iteration on the stream the kernels run on; median and minimum -------
+    def per_iteration_ms(fn, warm=5, iters=20):
+        for _ in range(warm):
+            fn()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+        torch.cuda.synchronize()
+        for e0, e1 in evs:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+        return 0.5 * (ms[(iters - 1) // 2] + ms[iters // 2]), ms[0]
+
     sweep = []
     for B, n in POINTS:
         t = views(B, n)
-        times = {}
-        for what in ("fwd", "bwd"):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            e0.record()
-            for _ in range(args.steps):
-                if what == "fwd":
-                    binding.la_fwd(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=ws)
-                else:
-                    binding.la_bwd(t["Q"], t["K"], t["V"], lam, t["dO"], dQ=t["dQ"], dK=t["dK"],
+        f = lambda: binding.la_fwd(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=ws)
+        b = lambda: binding.la_bwd(t["Q"], t["K"], t["V"], lam, t["dO"], dQ=t["dQ"], dK=t["dK"],
                                    dV=t["dV"], workspace=ws)
-            e1.record()
-            e1.synchronize()
-            times[what] = e0.elapsed_time(e1) / args.steps
-        tot_ms = times["fwd"] + times["bwd"]
-        tps = TOKENS / (tot_ms * 1e-3)
+        f_med, f_min = per_iteration_ms(f)
+        b_med, b_min = per_iteration_ms(b)
+        fb_med, fb_min = per_iteration_ms(lambda: (f(), b()))
+        tps = TOKENS / (fb_med * 1e-3)
         tflops = tps * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12
         _, L, S = binding.la_plan(B, H, n, D, binding.LA_BF16)
-        sweep.append({"B": B, "n": n, "fwd_ms": round(times["fwd"], 4), "bwd_ms": round(times["bwd"], 4),
+        sweep.append({"B": B, "n": n, "fwd_ms": round(f_med, 4), "fwd_ms_min": round(f_min, 4),
+                      "bwd_ms": round(b_med, 4), "bwd_ms_min": round(b_min, 4),
+                      "fwd_bwd_ms": round(fb_med, 4), "fwd_bwd_ms_min": round(fb_min, 4),
                       "tokens_per_s": round(tps, 1), "model_tflops": round(tflops, 2),
                       "pct_mfma_bf16_peak": round(100.0 * tflops / MFMA_BF16_PEAK_TFLOPS, 2),
                       "segment_len": L, "segments": S})
+    rates = [p["tokens_per_s"] for p in sweep]
+    near_constant = {"min_over_max_tokens_per_s": round(min(rates) / max(rates), 3),
+                     "note": "per-point rates from the median back-to-back fwd+bwd time of 20 iterations"}
 
     # ---- roofline of the dominant kernel: the block-scan kernel -------------------
     # One launch streams three [tokens, H, d] bf16 operands in and one out:
@@ -307,6 +317,7 @@ def main():
         "model_tflops": round(total_tflops, 2),
         "pct_mfma_bf16_peak": round(100.0 * total_tflops / MFMA_BF16_PEAK_TFLOPS, 2),
         "sweep": sweep,
+        "near_constant": near_constant,
         "roofline": roofline,
         "decode": decode,
         "gate_norm": gate_norm,
