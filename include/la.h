@@ -227,6 +227,39 @@ int la_lrpe_rotate_bwd(const void *X, const float *theta /* device, [H, d] */, c
                        void *workspace, size_t workspace_bytes,
                        int B, int H, int n, int d, la_dtype dt, void *hip_stream);
 
+/*
+ * la_fwd / la_bwd on tensors that are not contiguous [B, H, n, d]: the slab of
+ * (batch b, head h) starts b * batch_stride + h * head_stride elements after the
+ * pointer and its rows (d contiguous elements each) are row_stride elements apart.
+ * Contiguous [B, H, n, d] is {H n d, n d, d}; the [B, n, H, d] a projection GEMM
+ * writes is {n H d, d, H d}; Q, K, V packed as [B, n, 3, H, d] are three pointers d * H
+ * elements apart with {3 n H d, d, 3 H d}.  This is the paper's own situation: its
+ * layers produce Q, K, V as [B, n, H d] (Sec. 4.2, Q = phi(X W_q) ...) and the
+ * attention runs per head.  Q, K, V share one layout; O (forward), dO, and dQ, dK, dV
+ * (backward) have their own.  Strides are in elements, multiples of 8, row_stride
+ * >= d (else LA_ERR_ALIGN / LA_ERR_SHAPE); outputs must not overlap anything.
+ * Everything else as la_fwd / la_bwd; results are bit-identical to theirs.
+ */
+typedef struct la_layout {
+    long long batch_stride, head_stride, row_stride;
+} la_layout;
+
+int la_fwd_strided(const void *Q, const void *K, const void *V,
+                   const float *lambda /* host, [H] */,
+                   void *O,
+                   const la_layout *qkv_layout, const la_layout *o_layout,
+                   int B, int H, int n, int d, la_dtype dt,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+int la_bwd_strided(const void *Q, const void *K, const void *V,
+                   const float *lambda /* host, [H] */,
+                   const void *dO,
+                   void *dQ, void *dK, void *dV,
+                   const la_layout *qkv_layout, const la_layout *do_layout,
+                   const la_layout *grad_layout,
+                   int B, int H, int n, int d, la_dtype dt,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static, human-readable text for an la_status value. */
 const char *la_strerror(int status);
 

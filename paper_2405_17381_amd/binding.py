@@ -17,9 +17,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libla.so")
 EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_fwd_state", "la_decode_step", "la_gate_norm_fwd",
            "la_gate_norm_bwd", "la_fwd_swish", "la_bwd_swish", "la_fwd_wide", "la_bwd_wide", "la_lrpe_workspace_bytes",
-           "la_lrpe_rotate_fwd", "la_lrpe_rotate_bwd", "la_strerror", "la_plan",
+           "la_lrpe_rotate_fwd", "la_lrpe_rotate_bwd", "la_fwd_strided", "la_bwd_strided", "la_strerror", "la_plan",
            "la_profile_enable", "la_profile_collect")
 _lib = None
+
+
+class LaLayout(ctypes.Structure):
+    """la_layout of include/la.h: strides in elements."""
+    _fields_ = [("batch_stride", ctypes.c_longlong), ("head_stride", ctypes.c_longlong),
+                ("row_stride", ctypes.c_longlong)]
 
 
 class LaError(RuntimeError):
@@ -58,6 +64,11 @@ def load_library():
     lib.la_lrpe_rotate_fwd.restype = ci
     lib.la_lrpe_rotate_bwd.argtypes = [vp, vp, vp, vp, vp, ci, vp, sz, ci, ci, ci, ci, ci, vp]
     lib.la_lrpe_rotate_bwd.restype = ci
+    lp = ctypes.POINTER(LaLayout)
+    lib.la_fwd_strided.argtypes = [vp, vp, vp, fp, vp, lp, lp, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.la_fwd_strided.restype = ci
+    lib.la_bwd_strided.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, lp, lp, lp, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.la_bwd_strided.restype = ci
     lib.la_fwd_state.argtypes = [vp, vp, vp, fp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.la_fwd_state.restype = ci
     lib.la_decode_step.argtypes = [vp, vp, vp, fp, vp, vp, ci, ci, ci, ci, vp]
@@ -233,6 +244,60 @@ def la_bwd(Q, K, V, lam, dO, dQ=None, dK=None, dV=None, workspace: Optional[torc
 def la_bwd_swish(Qp, Kp, V, lam, dO, dQp=None, dKp=None, dV=None, workspace: Optional[torch.Tensor] = None):
     """Gradients of la_fwd_swish with respect to the pre-activations Qp, Kp and to V."""
     return la_bwd(Qp, Kp, V, lam, dO, dQ=dQp, dK=dKp, dV=dV, workspace=workspace, _entry="la_bwd_swish")
+
+
+def _layout_of(ts: Sequence[torch.Tensor]) -> LaLayout:
+    """Layout shared by [B, H, n, d]-shaped views (any batch / head / row strides, unit feature stride)."""
+    t0 = ts[0]
+    for t in ts:
+        if t.dim() != 4 or not t.is_cuda or t.shape != t0.shape or t.dtype != t0.dtype or t.device != t0.device:
+            raise ValueError("la: tensors must be [B, H, n, d] views of one shape, dtype and GPU")
+        if t.stride(3) != 1 or t.stride() != t0.stride():
+            raise ValueError("la: views must have unit feature stride and share their strides")
+    return LaLayout(t0.stride(0), t0.stride(1), t0.stride(2))
+
+
+def la_fwd_strided(Q, K, V, lam, O=None, workspace: Optional[torch.Tensor] = None):
+    """la_fwd on [B, H, n, d]-shaped views with arbitrary batch / head / row strides, e.g. the
+    permuted view of a [B, n, H, d] projection output.  O defaults to a view laid out like Q."""
+    lin = _layout_of([Q, K, V])
+    B, H, n, d = Q.shape
+    if O is None:
+        O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    lout = _layout_of([O])
+    dt = _dt(Q)
+    ws, ws_ptr, ws_bytes = _workspace(B, H, n, d, dt, False, Q.device, workspace)
+    with torch.cuda.device(Q.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_fwd_strided(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _lam(lam, H), O.data_ptr(),
+                                           ctypes.byref(lin), ctypes.byref(lout), B, H, n, d, dt,
+                                           ws_ptr, ws_bytes, stream)
+    if rc != 0:
+        raise LaError(rc, "la_fwd_strided")
+    return O
+
+
+def la_bwd_strided(Q, K, V, lam, dO, dQ=None, dK=None, dV=None, workspace: Optional[torch.Tensor] = None):
+    """la_bwd on strided [B, H, n, d]-shaped views; gradients default to views laid out like Q."""
+    lin = _layout_of([Q, K, V])
+    ldo = _layout_of([dO])
+    B, H, n, d = Q.shape
+    mk = lambda: torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    dQ = mk() if dQ is None else dQ
+    dK = mk() if dK is None else dK
+    dV = mk() if dV is None else dV
+    lgr = _layout_of([dQ, dK, dV])
+    dt = _dt(Q)
+    ws, ws_ptr, ws_bytes = _workspace(B, H, n, d, dt, True, Q.device, workspace)
+    with torch.cuda.device(Q.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_bwd_strided(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _lam(lam, H), dO.data_ptr(),
+                                           dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), ctypes.byref(lin),
+                                           ctypes.byref(ldo), ctypes.byref(lgr), B, H, n, d, dt,
+                                           ws_ptr, ws_bytes, stream)
+    if rc != 0:
+        raise LaError(rc, "la_bwd_strided")
+    return dQ, dK, dV
 
 
 def la_fwd_wide(Qw, Kw, V, lam, O=None, workspace: Optional[torch.Tensor] = None):

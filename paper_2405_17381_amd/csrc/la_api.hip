@@ -213,6 +213,8 @@ struct Variant {
     bool swish = false;     // Q, K are pre-activations (la_fwd_swish / la_bwd_swish)
     int wide_ld = 0;        // > 0: Q, K (and dQ, dK) are d-wide slices of rows this many elements wide
     bool accumulate = false; // the result over this slice is added to O (forward) / dV (backward)
+    // caller-given layouts (la_*_strided): Q, K, V / O (forward); Q, K, V / dO / dQ, dK, dV (backward)
+    const LaLayout *in = nullptr, *out = nullptr, *dout = nullptr;
 };
 
 ScanArgs make_args(const void *A, const void *Bm, const void *C, void *Out, const Plan &p,
@@ -299,6 +301,11 @@ int run_scan(const void *A, const void *Bm, const void *C, void *Out, const LaLa
         a.lA = a.lB = contiguous_layout(H, n, var.wide_ld);
         a.act |= LA_ACT_EXT | (var.accumulate ? LA_ACT_ACC : 0);
     }
+    if (var.in) {
+        a.lA = a.lB = a.lC = *var.in;
+        a.lO = *var.out;
+        a.act |= LA_ACT_EXT;
+    }
     a.B = B;
     a.rev = REV ? 1 : 0;
     a.st_in = st_in;
@@ -366,6 +373,12 @@ int run_backward(const void *Q, const void *K, const void *V, const void *dO, vo
         av.lA = av.lB = w;                                     // dV (+)= scan_rev(K slice, Q slice, dO)
         pre[0].act |= LA_ACT_EXT; pre[1].act |= LA_ACT_EXT;
         av.act |= LA_ACT_EXT | (var.accumulate ? LA_ACT_ACC : 0);
+    }
+    if (var.in) {
+        pre[0].lA = *var.dout; pre[0].lB = pre[0].lC = *var.in; pre[0].lO = *var.out;   // scan(dO, V, K) -> dQ
+        pre[1].lA = *var.in; pre[1].lB = *var.dout; pre[1].lC = *var.in; pre[1].lO = *var.out;  // (V, dO, Q) -> dK
+        av.lA = av.lB = *var.in; av.lC = *var.dout; av.lO = *var.out;                   // (K, Q, dO) -> dV
+        pre[0].act |= LA_ACT_EXT; pre[1].act |= LA_ACT_EXT; av.act |= LA_ACT_EXT;
     }
     if (p.S > 1) {
         int rc = run_prepass(pre, 2, lams, scans, d, dt, s);
@@ -458,6 +471,17 @@ int backward(const void *Q, const void *K, const void *V, const float *lambda, c
                         (hipStream_t)hip_stream, var);
 }
 
+// Caller-given layout: 16-byte granularity everywhere, rows at least d apart.
+int check_layout(const la_layout *l, int d, LaLayout *out)
+{
+    if (!l) return LA_ERR_NULL;
+    if (l->row_stride < d || l->batch_stride < 0 || l->head_stride < 0) return LA_ERR_SHAPE;
+    if (l->row_stride % 8 || l->batch_stride % 8 || l->head_stride % 8) return LA_ERR_ALIGN;
+    if (l->row_stride > INT32_MAX) return LA_ERR_SHAPE;
+    out->bs = (long)l->batch_stride; out->hs = (long)l->head_stride; out->ld = (int)l->row_stride;
+    return LA_OK;
+}
+
 // d_k = m * d_v: the scores add over the m slices of the query / key features, so the
 // attention is the sum of m ordinary ones (App. A's kv state becomes m d_v x d_v states).
 int check_wide(int dk, int dv)
@@ -514,6 +538,21 @@ int la_fwd_swish(const void *Qp, const void *Kp, const void *V, const float *lam
     Variant var;
     var.swish = true;
     return forward(Qp, Kp, V, lambda, O, nullptr, nullptr, B, H, n, d, dt, workspace, workspace_bytes,
+                   hip_stream, var);
+}
+
+int la_fwd_strided(const void *Q, const void *K, const void *V, const float *lambda, void *O,
+                   const la_layout *qkv_layout, const la_layout *o_layout,
+                   int B, int H, int n, int d, la_dtype dt,
+                   void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    LaLayout in, out;
+    int rc = check_layout(qkv_layout, d, &in);
+    if (rc == LA_OK) rc = check_layout(o_layout, d, &out);
+    if (rc != LA_OK) return rc;
+    Variant var;
+    var.in = &in; var.out = &out;
+    return forward(Q, K, V, lambda, O, nullptr, nullptr, B, H, n, d, dt, workspace, workspace_bytes,
                    hip_stream, var);
 }
 
@@ -577,6 +616,23 @@ int la_bwd_swish(const void *Qp, const void *Kp, const void *V, const float *lam
     Variant var;
     var.swish = true;
     return backward(Qp, Kp, V, lambda, dO, dQp, dKp, dV, B, H, n, d, dt, workspace, workspace_bytes,
+                    hip_stream, var);
+}
+
+int la_bwd_strided(const void *Q, const void *K, const void *V, const float *lambda, const void *dO,
+                   void *dQ, void *dK, void *dV,
+                   const la_layout *qkv_layout, const la_layout *do_layout, const la_layout *grad_layout,
+                   int B, int H, int n, int d, la_dtype dt,
+                   void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    LaLayout in, dout, out;
+    int rc = check_layout(qkv_layout, d, &in);
+    if (rc == LA_OK) rc = check_layout(do_layout, d, &dout);
+    if (rc == LA_OK) rc = check_layout(grad_layout, d, &out);
+    if (rc != LA_OK) return rc;
+    Variant var;
+    var.in = &in; var.dout = &dout; var.out = &out;
+    return backward(Q, K, V, lambda, dO, dQ, dK, dV, B, H, n, d, dt, workspace, workspace_bytes,
                     hip_stream, var);
 }
 

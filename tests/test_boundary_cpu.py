@@ -136,3 +136,12 @@ def test_inference_and_output_stage_entry_points_reject_bad_arguments():
     assert lib.la_lrpe_rotate_bwd(P, P, P, P, P, 0, 0, 0, 1, 1, 8, 64, 1, None) == -5
     assert lib.la_lrpe_rotate_bwd(P, P, P, P, P, 0, P, 16, 1, 1, 8, 64, 1, None) == -5
     assert lib.la_lrpe_rotate_bwd(P, P, P, P, 0, 0, P, 1 << 20, 1, 1, 8, 64, 1, None) == -1
+    # strided layouts: strides in multiples of 8 elements, rows at least d apart
+    good = binding.LaLayout(8 * 64 * 2, 64, 2 * 64)
+    short = binding.LaLayout(8 * 64, 64, 32)
+    odd = binding.LaLayout(8 * 64 * 2 + 4, 64, 2 * 64)
+    ref = ctypes.byref
+    assert lib.la_fwd_strided(P, P, P, lam, P, ref(good), None, 1, 2, 8, 64, 1, 0, 0, None) == -1
+    assert lib.la_fwd_strided(P, P, P, lam, P, ref(short), ref(good), 1, 2, 8, 64, 1, 0, 0, None) == -2
+    assert lib.la_fwd_strided(P, P, P, lam, P, ref(good), ref(odd), 1, 2, 8, 64, 1, 0, 0, None) == -7
+    assert lib.la_bwd_strided(P, P, P, lam, P, P, P, P, ref(good), ref(good), ref(short), 1, 2, 8, 64, 1, 0, 0, None) == -2
