@@ -302,6 +302,21 @@ def main():
                     "path's traffic plus the accumulator re-reads); rotation: 1 tensor in, 2 out (forward), "
                     "3 in, 1 out (backward)"}
 
+    # ---- fp32 path (matrix-core fp32 kernel at d = 128): the (32, 2048) point in fp32 ---------------
+    fB, fn = 32, 2048
+    ft = {k: flat[k][: fB * H * fn * D].float().view(fB, H, fn, D) for k in ("Q", "K", "V", "dO")}
+    fo = [torch.empty_like(ft["Q"]) for _ in range(4)]
+    ff = _time(lambda: binding.la_fwd(ft["Q"], ft["K"], ft["V"], lam, O=fo[0]))
+    fb = _time(lambda: binding.la_bwd(ft["Q"], ft["K"], ft["V"], lam, ft["dO"], dQ=fo[1], dK=fo[2], dV=fo[3]))
+    f_tps = fB * fn / ((ff + fb) * 1e-3)
+    fp32_path = {"workload": "la_fwd + la_bwd in fp32, [32,16,2048,128]", "fwd_ms": round(ff, 4), "bwd_ms": round(fb, 4),
+                 "tokens_per_s": round(f_tps, 1),
+                 "model_tflops": round(f_tps * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12, 2),
+                 "executed_tflops": round(f_tps * H * (4 * (4 * 32 * D + 4 * D * D)) / 1e12, 2),
+                 "note": "compute-bound (fp32 MFMA peak 157.3 TFLOP/s); executed flops = four scans of "
+                         "4 BK d + 4 d^2 per token per head at BK = 32"}
+    del ft, fo
+
     total_tflops = value * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12
     out = {
         "metric": "fwd+bwd tokens/s (causal linear attention with decay, bf16, d=128, seq-len sweep "
@@ -323,6 +338,7 @@ def main():
         "gate_norm": gate_norm,
         "swish_fused": swish_fused,
         "lrpe_d": lrpe,
+        "fp32_path": fp32_path,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()

@@ -10,6 +10,7 @@
 #include "la_common.h"
 #include "la_kernels_bf16.h"
 #include "la_kernels_f32.h"
+#include "la_kernels_f32m.h"
 #include "la_kernels_gate.h"
 #include "la_kernels_lrpe.h"
 #include "la_kernels_misc.h"
@@ -183,6 +184,20 @@ hipError_t launch_f32(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
     return hipGetLastError();
 }
 
+template <int D, bool REV, bool STATE_ONLY>
+hipError_t launch_f32m(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
+{
+    using Cfg = F32mCfg<D>;
+    auto kern = la_scan_f32m<D, REV, STATE_ONLY>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
+    if (attr_err != hipSuccess) return attr_err;
+    dim3 grid((unsigned)(a.items * a.nroles)), block(Cfg::NT);   // roles one after the other
+    hipLaunchKernelGGL(kern, grid, block, Cfg::lds_bytes, s, a, lams);
+    return hipGetLastError();
+}
+
 template <bool REV, bool STATE_ONLY>
 hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
                               la_dtype dt, hipStream_t s)
@@ -197,8 +212,11 @@ hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
         if (act) return d == 64 ? launch_bf16<64, REV, true>(a, lams, s) : launch_bf16<128, REV, true>(a, lams, s);
         return d == 64 ? launch_bf16<64, REV, false>(a, lams, s) : launch_bf16<128, REV, false>(a, lams, s);
     }
+    // fp32: d = 64 runs the literal FMA kernel with 64-row blocks; d = 128 the matrix-core kernel
+    // (32-row blocks; LA_F32_PLAIN selects the FMA kernel there too, for comparisons)
     if (d == 64) return launch_f32<64, 64, REV, STATE_ONLY>(a, lams, s);
-    return launch_f32<128, 32, REV, STATE_ONLY>(a, lams, s);
+    if (std::getenv("LA_F32_PLAIN")) return launch_f32<128, 32, REV, STATE_ONLY>(a, lams, s);
+    return launch_f32m<128, REV, STATE_ONLY>(a, lams, s);
 }
 
 LaLayout contiguous_layout(int H, int n, int d)

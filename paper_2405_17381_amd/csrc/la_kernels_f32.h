@@ -1,7 +1,9 @@
 // fp32 path: the block loop of Alg. 5 / Alg. 6 taken literally, all-fp32 FMA
 // arithmetic, one workgroup of 256 threads per (scan, segment).  Tiles of A,
 // Bm, C, the masked score tile and the running state all live in LDS.
-// This path exists for fp32 parity (tolerance 1e-4), not for speed.
+// This kernel exists for fp32 parity (tolerance 1e-4), not for speed: it serves d = 64
+// (64-row blocks) and, when LA_F32_PLAIN is set, d = 128 as a second implementation to
+// compare the matrix-core fp32 kernel (la_kernels_f32m.h) against.
 #pragma once
 #include "la_common.h"
 

@@ -157,6 +157,24 @@ def test_decay_cutoff_of_the_prepass_is_invisible():
     _full_case(wf, lseg=256)
 
 
+def test_fp32_matrix_core_kernel_against_the_plain_fma_kernel():
+    """d = 128 in fp32 runs on v_mfma_f32_32x32x2_f32; LA_F32_PLAIN selects the literal FMA kernel.
+    Two implementations of the same fp32 arithmetic: they differ by summation order only."""
+    lam = [1.0, 0.999, 0.9, 0.3]
+    w = synth.custom(2, 4, 777, 128, lam, seed=41, dtype="f32")
+    xs = synth.draw(w)
+    for lseg in (None, 256):
+        mfma = _run_gpu(w, xs, lseg=lseg)
+        os.environ["LA_F32_PLAIN"] = "1"
+        try:
+            plain = _run_gpu(w, xs, lseg=lseg)
+        finally:
+            os.environ.pop("LA_F32_PLAIN", None)
+        for a, b in zip(mfma, plain):
+            assert oracle.rel_max_err(a, b) <= 5e-6
+            assert not np.array_equal(a, b)          # they really are different kernels
+
+
 def test_bitwise_reproducible():
     w = synth.custom(2, 4, 1500, 128, [1.0, 0.99, 0.9, 0.5], seed=5, dtype="bf16")
     xs = synth.draw(w)
