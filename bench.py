@@ -302,6 +302,20 @@ def main():
                     "path's traffic plus the accumulator re-reads); rotation: 1 tensor in, 2 out (forward), "
                     "3 in, 1 out (backward)"}
 
+    # ---- training step that keeps the forward workspace: la_fwd + la_bwd_saved, (1, 65536) point -----
+    t = views(1, TOKENS)
+    fws = torch.empty(max(256, binding.la_workspace_bytes(1, H, TOKENS, D, binding.LA_BF16, False)),
+                      dtype=torch.uint8, device=dev)
+    def train_step():
+        binding.la_fwd(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=fws)
+        binding.la_bwd_saved(t["Q"], t["K"], t["V"], lam, t["dO"], fws, dQ=t["dQ"], dK=t["dK"], dV=t["dV"],
+                             workspace=ws)
+    sv = _time(train_step, it=20)
+    saved_states = {"workload": "la_fwd + la_bwd_saved (backward reuses the forward pass's segment states), "
+                                "[1,16,65536,128] bf16",
+                    "fwd_bwd_ms": round(sv, 4), "tokens_per_s": round(TOKENS / (sv * 1e-3), 1),
+                    "plain_fwd_bwd_ms": sweep[-1]["fwd_bwd_ms"] if sweep[-1]["n"] == TOKENS else None}
+
     # ---- fp32 path (matrix-core fp32 kernel at d = 128): the (32, 2048) point in fp32 ---------------
     fB, fn = 32, 2048
     ft = {k: flat[k][: fB * H * fn * D].float().view(fB, H, fn, D) for k in ("Q", "K", "V", "dO")}
@@ -339,6 +353,7 @@ def main():
         "swish_fused": swish_fused,
         "lrpe_d": lrpe,
         "fp32_path": fp32_path,
+        "saved_states": saved_states,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()

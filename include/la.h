@@ -103,6 +103,27 @@ int la_bwd(const void *Q, const void *K, const void *V,
            void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Backward pass that reuses what the forward pass already computed.  When a sequence
+ * is cut into segments (la_workspace_bytes(..., 0) > 0), la_fwd leaves the segment
+ * states of scan(Q, K, V) in its workspace; the dQ scan of the backward pass needs
+ * exactly their transposes (App. C: both are the KV state at segment boundaries).
+ * `fwd_workspace` is the buffer a completed la_fwd call with the same Q, K, V, lambda,
+ * B, H, n, d, dt used, unmodified since; it is only read.  `workspace` then needs only
+ * la_workspace_bytes(..., is_bwd = 0) bytes (the reverse states) and must be a
+ * different buffer.  Results equal la_bwd's up to the rounding order of those states.
+ * When no segmentation is needed (that query returns 0) both may be NULL and this is
+ * la_bwd.  A training step that keeps the forward workspace saves half of the
+ * backward pre-pass.
+ */
+int la_bwd_saved(const void *Q, const void *K, const void *V,
+                 const float *lambda /* host, [H] */,
+                 const void *dO,
+                 void *dQ, void *dK, void *dV,
+                 const void *fwd_workspace,
+                 int B, int H, int n, int d, la_dtype dt,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Forward pass with a carried state (the next step after la_fwd / la_bwd: the
  * paper's inference use, Sec. 3.1, where only the d x d state K^T V is kept
  * between calls; the recurrence is App. A's with kv_0 = kv_in):

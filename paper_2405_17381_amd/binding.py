@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libla.so")
 EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_fwd_state", "la_decode_step", "la_gate_norm_fwd",
            "la_gate_norm_bwd", "la_fwd_swish", "la_bwd_swish", "la_fwd_wide", "la_bwd_wide", "la_lrpe_workspace_bytes",
-           "la_lrpe_rotate_fwd", "la_lrpe_rotate_bwd", "la_fwd_strided", "la_bwd_strided", "la_strerror", "la_plan",
+           "la_lrpe_rotate_fwd", "la_lrpe_rotate_bwd", "la_fwd_strided", "la_bwd_strided", "la_bwd_saved", "la_strerror", "la_plan",
            "la_profile_enable", "la_profile_collect")
 _lib = None
 
@@ -69,6 +69,8 @@ def load_library():
     lib.la_fwd_strided.restype = ci
     lib.la_bwd_strided.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, lp, lp, lp, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.la_bwd_strided.restype = ci
+    lib.la_bwd_saved.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.la_bwd_saved.restype = ci
     lib.la_fwd_state.argtypes = [vp, vp, vp, fp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.la_fwd_state.restype = ci
     lib.la_decode_step.argtypes = [vp, vp, vp, fp, vp, vp, ci, ci, ci, ci, vp]
@@ -238,6 +240,28 @@ def la_bwd(Q, K, V, lam, dO, dQ=None, dK=None, dV=None, workspace: Optional[torc
                                              B, H, n, d, dt, ws_ptr, ws_bytes, stream)
     if rc != 0:
         raise LaError(rc, _entry)
+    return dQ, dK, dV
+
+
+def la_bwd_saved(Q, K, V, lam, dO, fwd_workspace, dQ=None, dK=None, dV=None,
+                 workspace: Optional[torch.Tensor] = None):
+    """la_bwd reusing the segment states that la_fwd(Q, K, V, lam, workspace=fwd_workspace) left behind."""
+    _check([Q, K, V, dO])
+    B, H, n, d = Q.shape
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    _check([Q, dQ, dK, dV])
+    dt = _dt(Q)
+    ws, ws_ptr, ws_bytes = _workspace(B, H, n, d, dt, False, Q.device, workspace)
+    fptr = fwd_workspace.data_ptr() if fwd_workspace is not None else None
+    with torch.cuda.device(Q.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_bwd_saved(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _lam(lam, H), dO.data_ptr(),
+                                         dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), fptr,
+                                         B, H, n, d, dt, ws_ptr, ws_bytes, stream)
+    if rc != 0:
+        raise LaError(rc, "la_bwd_saved")
     return dQ, dK, dV
 
 

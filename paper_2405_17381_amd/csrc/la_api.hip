@@ -233,6 +233,9 @@ struct Variant {
     bool accumulate = false; // the result over this slice is added to O (forward) / dV (backward)
     // caller-given layouts (la_*_strided): Q, K, V / O (forward); Q, K, V / dO / dQ, dK, dV (backward)
     const LaLayout *in = nullptr, *out = nullptr, *dout = nullptr;
+    // backward only: the segment states la_fwd left in its workspace for the same problem
+    // (la_bwd_saved); the dQ scan reads them transposed instead of recomputing them
+    const float *fwd_states = nullptr;
 };
 
 ScanArgs make_args(const void *A, const void *Bm, const void *C, void *Out, const Plan &p,
@@ -369,10 +372,12 @@ int run_backward(const void *Q, const void *K, const void *V, const void *dO, vo
                  la_dtype dt, float *ws, hipStream_t s, const Variant &var)
 {
     const long scans = (long)B * H;
-    float *ws_f = ws;
-    float *ws_r = ws ? ws + (size_t)scans * p.S * (size_t)d * d : nullptr;
+    // la_fwd's states are those of scan(., K, V); the dQ scan wants scan(., V, K): the transposes
+    const bool reuse = var.fwd_states != nullptr && p.S > 1;
+    float *ws_f = reuse ? const_cast<float *>(var.fwd_states) : ws;
+    float *ws_r = reuse ? ws : (ws ? ws + (size_t)scans * p.S * (size_t)d * d : nullptr);
     ScanArgs pre[2];
-    pre[0] = make_args(dO, V, K, dQ, p, H, n, d, dt, ws_f, 0);
+    pre[0] = make_args(dO, V, K, dQ, p, H, n, d, dt, ws_f, reuse ? 1 : 0);
     pre[1] = make_args(V, dO, Q, dK, p, H, n, d, dt, ws_r, 0);
     pre[1].rev = 1;
     pre[0].B = pre[1].B = B;
@@ -399,8 +404,14 @@ int run_backward(const void *Q, const void *K, const void *V, const void *dO, vo
         pre[0].act |= LA_ACT_EXT; pre[1].act |= LA_ACT_EXT; av.act |= LA_ACT_EXT;
     }
     if (p.S > 1) {
-        int rc = run_prepass(pre, 2, lams, scans, d, dt, s);
-        if (rc == LA_OK) rc = run_segment_scan_pair(pre[0], pre[1], lams, scans, d, s);
+        int rc;
+        if (reuse) {
+            rc = run_prepass(&pre[1], 1, lams, scans, d, dt, s);
+            if (rc == LA_OK) rc = run_segment_scan<true>(pre[1], lams, scans, d, s);
+        } else {
+            rc = run_prepass(pre, 2, lams, scans, d, dt, s);
+            if (rc == LA_OK) rc = run_segment_scan_pair(pre[0], pre[1], lams, scans, d, s);
+        }
         if (rc != LA_OK) return rc;
     }
     int rc = run_block_scan<false>(pre[0], lams, scans, d, dt, s);
@@ -483,7 +494,7 @@ int backward(const void *Q, const void *K, const void *V, const float *lambda, c
     rc = check_lambda(lambda, H, &lams);
     if (rc != LA_OK) return rc;
     const Plan p = make_plan(B, H, n, d, dt);
-    rc = check_workspace(p, B, H, d, workspace, workspace_bytes, true);
+    rc = check_workspace(p, B, H, d, workspace, workspace_bytes, var.fwd_states == nullptr);
     if (rc != LA_OK) return rc;
     return run_backward(Q, K, V, dO, dQ, dK, dV, lams, p, B, H, n, d, dt, (float *)workspace,
                         (hipStream_t)hip_stream, var);
@@ -624,6 +635,20 @@ int la_bwd(const void *Q, const void *K, const void *V, const float *lambda, con
 {
     return backward(Q, K, V, lambda, dO, dQ, dK, dV, B, H, n, d, dt, workspace, workspace_bytes,
                     hip_stream, Variant());
+}
+
+int la_bwd_saved(const void *Q, const void *K, const void *V, const float *lambda, const void *dO,
+                 void *dQ, void *dK, void *dV, const void *fwd_workspace,
+                 int B, int H, int n, int d, la_dtype dt,
+                 void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Variant var;
+    if (la_workspace_bytes(B, H, n, d, dt, 0) > 0) {
+        if (!fwd_workspace || ((uintptr_t)fwd_workspace & 255u)) return LA_ERR_WORKSPACE;
+        var.fwd_states = (const float *)fwd_workspace;
+    }
+    return backward(Q, K, V, lambda, dO, dQ, dK, dV, B, H, n, d, dt, workspace, workspace_bytes,
+                    hip_stream, var);
 }
 
 int la_bwd_swish(const void *Qp, const void *Kp, const void *V, const float *lambda, const void *dO,

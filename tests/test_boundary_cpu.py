@@ -145,3 +145,11 @@ def test_inference_and_output_stage_entry_points_reject_bad_arguments():
     assert lib.la_fwd_strided(P, P, P, lam, P, ref(short), ref(good), 1, 2, 8, 64, 1, 0, 0, None) == -2
     assert lib.la_fwd_strided(P, P, P, lam, P, ref(good), ref(odd), 1, 2, 8, 64, 1, 0, 0, None) == -7
     assert lib.la_bwd_strided(P, P, P, lam, P, P, P, P, ref(good), ref(good), ref(short), 1, 2, 8, 64, 1, 0, 0, None) == -2
+    # la_bwd_saved: a segmented problem needs the forward workspace
+    import os
+    os.environ["LA_LSEG"] = "64"
+    try:
+        assert lib.la_bwd_saved(P, P, P, lam, P, P, P, P, 0, 1, 1, 256, 64, 1, P, 1 << 30, None) == -5
+        assert lib.la_bwd_saved(P, P, P, lam, P, P, P, P, P + 8, 1, 1, 256, 64, 1, P, 1 << 30, None) == -5
+    finally:
+        os.environ.pop("LA_LSEG", None)

@@ -338,3 +338,35 @@ def test_hip_graph_capture_and_replay():
             assert torch.equal(o, r)
     finally:
         os.environ.pop("LA_LSEG", None)
+
+
+@pytest.mark.parametrize("dtype,d,n,lseg", [("bf16", 128, 5000, None), ("bf16", 64, 1500, 256), ("f32", 128, 700, 128),
+                                             ("f32", 64, 900, 256), ("bf16", 128, 300, None)])
+def test_backward_reusing_the_forward_states(dtype, d, n, lseg):
+    """la_bwd_saved takes the segment states la_fwd left in its workspace instead of recomputing
+    them: same gradients as la_bwd (up to the rounding order of those states), and the oracle's."""
+    lam = [1.0, 0.9995, 0.98, 0.6]
+    w = synth.custom(1, 4, n, d, lam, seed=900 + n, dtype=dtype)
+    xs = synth.draw(w)
+    if lseg is not None:
+        os.environ["LA_LSEG"] = str(lseg)
+    try:
+        Q, K, V, dO = _to_dev(xs, dtype)
+        dt = binding.LA_BF16 if dtype == "bf16" else binding.LA_F32
+        need = binding.la_workspace_bytes(w.B, w.H, n, d, dt, False)
+        fws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        O = binding.la_fwd(Q, K, V, w.lambdas, workspace=fws)
+        keep = fws.clone()
+        got = binding.la_bwd_saved(Q, K, V, w.lambdas, dO, fws if need else None)
+        plain = binding.la_bwd(Q, K, V, w.lambdas, dO)
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("LA_LSEG", None)
+    assert torch.equal(fws, keep)                        # the forward workspace is only read
+    q, k, v, g = _ref_inputs(xs, dtype)
+    ref = oracle.c_recurrence_bwd(q, k, v, w.lambdas, g)
+    for nm, a, b, r in zip(("dQ", "dK", "dV"), got, plain, ref):
+        a64, b64 = a.double().cpu().numpy(), b.double().cpu().numpy()
+        assert oracle.rel_max_err(a64, r) <= TOL[dtype], nm
+        assert oracle.rel_max_err(a64, b64) <= (1e-5 if dtype == "f32" else 4e-3), nm
+    assert torch.equal(got[1], plain[1]) and torch.equal(got[2], plain[2])     # dK, dV: same code path
