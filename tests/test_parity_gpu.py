@@ -370,3 +370,15 @@ def test_backward_reusing_the_forward_states(dtype, d, n, lseg):
         assert oracle.rel_max_err(a64, r) <= TOL[dtype], nm
         assert oracle.rel_max_err(a64, b64) <= (1e-5 if dtype == "f32" else 4e-3), nm
     assert torch.equal(got[1], plain[1]) and torch.equal(got[2], plain[2])     # dK, dV: same code path
+
+
+def test_very_long_sequence_many_segments():
+    """One batch, two heads, 300 000 tokens: the planner cuts each scan into about 250 segments
+    (a ragged last one); lambda = 1 accumulates over all of them."""
+    lam = [1.0, 0.9999]
+    n = 300_000
+    w = synth.custom(1, 2, n, 128, lam, seed=5, dtype="bf16")
+    tile, L, S = binding.la_plan(1, 2, n, 128, binding.LA_BF16)
+    assert S > 200 and n % L != 0
+    _say("plan (tile, L, S) = %s" % ((tile, L, S),))
+    _full_case(w)
