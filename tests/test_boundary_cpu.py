@@ -153,3 +153,31 @@ def test_inference_and_output_stage_entry_points_reject_bad_arguments():
         assert lib.la_bwd_saved(P, P, P, lam, P, P, P, P, P + 8, 1, 1, 256, 64, 1, P, 1 << 30, None) == -5
     finally:
         os.environ.pop("LA_LSEG", None)
+
+
+def test_planner_properties(monkeypatch):
+    """For any valid shape: the segment length is a multiple of the tile, the segments cover the
+    sequence exactly, many scans are never cut, few scans are cut until two workgroups per compute
+    unit exist (or the 512-token floor is reached), and the scratch query matches the plan."""
+    import random
+    monkeypatch.delenv("LA_LSEG", raising=False)
+    rng = random.Random(7)
+    for _ in range(400):
+        B = rng.choice([1, 2, 3, 8, 31, 64, 300])
+        H = rng.choice([1, 2, 7, 16, 32, 256])
+        n = rng.choice([1, 63, 64, 65, 511, 512, 513, 2048, 5000, 65536, 131072, 1000003])
+        d = rng.choice([64, 128])
+        dt = rng.choice([binding.LA_F32, binding.LA_BF16])
+        tile, L, S = binding.la_plan(B, H, n, d, dt)
+        assert tile in (32, 64) and L % tile == 0 and S >= 1
+        assert (S - 1) * L < n <= S * L
+        scans = B * H
+        if scans >= 256:
+            assert S == 1
+        elif S > 1:
+            assert L >= 512
+            # (rounding the segment length up to the tile can cost one segment per scan)
+            assert scans * (S + 1) >= 512 or L < 512 + tile
+        need = binding.la_workspace_bytes(B, H, n, d, dt, False)
+        assert need == (scans * S * d * d * 4 if S > 1 else 0)
+        assert binding.la_workspace_bytes(B, H, n, d, dt, True) == 2 * need
