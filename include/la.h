@@ -23,7 +23,7 @@
  *     overwritten (never accumulated into).  Inputs and outputs must not alias.
  *   - `lambda` is a HOST pointer to H floats; it is read during the call and
  *     need not outlive it.  Every entry must be finite with 0 < lambda <= 1.
- *   - d is 64 or 128; B, H, n >= 1; H <= LA_MAX_HEADS.  n need not be a
+ *   - d is 64 or 128; B, H, n >= 1; H <= LA_MAX_HEADS; n <= LA_MAX_SEQ_LEN.  n need not be a
  *     multiple of the tile length: the tail behaves as if zero-padded, which
  *     is exact.
  *   - dt = LA_BF16: tensors are bfloat16; contractions use bf16 operands with
@@ -40,7 +40,10 @@
  *     reports a failed kernel launch part-way through the call.
  *   - Calls are thread-safe (no global mutable state apart from the optional
  *     profiling hooks below) and results are bitwise reproducible from run to
- *     run: no atomics are used in any reduction.
+ *     run: no atomics are used in any reduction.  The environment is never read.
+ *   - The launch planner is written for MI355X: it assumes 256 compute units when it
+ *     decides whether, and how finely, a sequence is cut into segments.  On a part
+ *     with another count the results are the same, only the occupancy differs.
  */
 #ifndef LA_H
 #define LA_H
@@ -52,6 +55,7 @@ extern "C" {
 #endif
 
 #define LA_MAX_HEADS 256
+#define LA_MAX_SEQ_LEN 2147483519   /* 2^31 - 1 - 128: longer n gives LA_ERR_SHAPE */
 
 typedef enum { LA_F32 = 0, LA_BF16 = 1 } la_dtype;
 
@@ -202,9 +206,10 @@ int la_bwd_swish(const void *Qp, const void *Kp, const void *V,
 /*
  * Attention whose query / key feature is wider than its value feature, d_k = m d_v
  * (m = 1..4), as the cos / sin features of LRPE-d give (Sec. 4.1, "Position
- * Encoding": the score q_t^T k_s lambda^(t-s) exp(i theta (t-s)) "can be decomposed
- * with respect to s and t": with x~_t = [x_t cos(t theta), x_t sin(t theta)] it is the
- * plain score q~_t^T k~_s lambda^(t-s) over 2d features):
+ * Encoding": the phase factor exp(i theta (t-s)) of the score q_t^T k_s lambda^(t-s)
+ * exp(i theta (t-s)) splits into a factor in t and a factor in s, so with
+ * x~_t = [x_t cos(t theta), x_t sin(t theta)] its real part is the plain score
+ * q~_t^T k~_s lambda^(t-s) over 2d features):
  *     O[t] = sum_{s <= t} lambda^(t-s) (Qw[t] . Kw[s]) V[s]
  * and its gradients.  Qw, Kw, dQw, dKw: [B, H, n, dk]; V, O, dO, dV: [B, H, n, dv];
  * dv is 64 or 128.  The scores add over the m slices of dv features, so the result
@@ -297,7 +302,10 @@ int la_plan(int B, int H, int n, int d, la_dtype dt,
  * Optional profiling hooks for benchmarks.  While enabled, every la_fwd /
  * la_bwd call brackets each launch of its block-scan kernel (the kernel that
  * runs the loops of Alg. 5 / Alg. 6) with HIP events on the call's stream.
- * la_profile_collect waits for those events, adds up the elapsed times and
+ * la_profile_enable(1) creates the events (the only place where the library
+ * creates anything; the forward / backward calls only record into them) and may
+ * return LA_ERR_LAUNCH if that fails; la_profile_enable(0) stops recording.
+ * la_profile_collect waits for the recorded events, adds up the elapsed times and
  * launch counts recorded since the last collect, and clears them.
  * Not thread-safe; meant for a single benchmarking thread.  At most
  * LA_PROFILE_MAX_LAUNCHES launches are recorded between collects; further

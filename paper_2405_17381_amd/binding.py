@@ -6,6 +6,7 @@ missing this module raises; there is no CPU fallback.
 """
 from __future__ import annotations
 
+import contextlib
 import ctypes
 import os
 from typing import Optional, Sequence, Tuple
@@ -19,6 +20,8 @@ EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_fwd_state", "la_decode_
            "la_gate_norm_bwd", "la_fwd_swish", "la_bwd_swish", "la_fwd_wide", "la_bwd_wide", "la_lrpe_workspace_bytes",
            "la_lrpe_rotate_fwd", "la_lrpe_rotate_bwd", "la_fwd_strided", "la_bwd_strided", "la_bwd_saved", "la_strerror", "la_plan",
            "la_profile_enable", "la_profile_collect")
+# exported for tests and tuning, declared in csrc/la_debug.h, not in include/la.h
+DEBUG_EXPORTS = ("la_debug_set", "la_debug_get")
 _lib = None
 
 
@@ -50,6 +53,10 @@ def load_library():
     lib.la_fwd.restype = ci
     lib.la_bwd.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.la_bwd.restype = ci
+    lib.la_debug_set.argtypes = [ctypes.c_char_p, ctypes.c_long]
+    lib.la_debug_set.restype = ci
+    lib.la_debug_get.argtypes = [ctypes.c_char_p]
+    lib.la_debug_get.restype = ctypes.c_long
     lib.la_fwd_swish.argtypes = lib.la_fwd.argtypes
     lib.la_fwd_swish.restype = ci
     lib.la_bwd_swish.argtypes = lib.la_bwd.argtypes
@@ -164,6 +171,29 @@ def la_fwd(Q, K, V, lam, O=None, workspace: Optional[torch.Tensor] = None, _entr
     if rc != 0:
         raise LaError(rc, _entry)
     return O
+
+
+def debug_set(name: str, value: int) -> None:
+    """Set a test / tuning switch of the library (csrc/la_debug.h); 0 restores the default."""
+    rc = load_library().la_debug_set(name.encode(), int(value))
+    if rc != 0:
+        raise LaError(rc, "la_debug_set(%s)" % name)
+
+
+def debug_get(name: str) -> int:
+    return int(load_library().la_debug_get(name.encode()))
+
+
+@contextlib.contextmanager
+def debug(**switches):
+    """`with binding.debug(lseg=512): ...` sets switches for the block and clears them after."""
+    for k, v in switches.items():
+        debug_set(k, 0 if v is None else v)
+    try:
+        yield
+    finally:
+        for k in switches:
+            debug_set(k, 0)
 
 
 def la_fwd_swish(Qp, Kp, V, lam, O=None, workspace: Optional[torch.Tensor] = None):

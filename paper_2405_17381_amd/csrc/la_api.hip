@@ -2,12 +2,14 @@
 // Declarations and the contract of every entry point are in include/la.h.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
-#include <cstdlib>
+#include <cstring>
 #include <mutex>
 
 #include "la_common.h"
+#include "la_debug.h"
 #include "la_kernels_bf16.h"
 #include "la_kernels_f32.h"
 #include "la_kernels_f32m.h"
@@ -17,6 +19,26 @@
 #include "la_kernels_prepass.h"
 
 namespace {
+
+// Test / tuning switches.  They are process-wide, start at zero, never look at the
+// environment and change only through la_debug_set (la_debug.h, not part of the public
+// header): the workspace query and the launch that follows therefore always plan alike.
+struct Switches {
+    std::atomic<long> lseg{0};           // > 0: segment length in tokens
+    std::atomic<long> no_pair{0};        // != 0: the dK and dV scans are launched separately
+    std::atomic<long> no_decay_skip{0};  // != 0: the segment-state pre-pass reads every block
+    std::atomic<long> f32_plain{0};      // != 0: fp32 at d = 128 runs the FMA kernel
+} g_sw;
+
+std::atomic<long> *find_switch(const char *name)
+{
+    if (!name) return nullptr;
+    if (!std::strcmp(name, "lseg")) return &g_sw.lseg;
+    if (!std::strcmp(name, "no_pair")) return &g_sw.no_pair;
+    if (!std::strcmp(name, "no_decay_skip")) return &g_sw.no_decay_skip;
+    if (!std::strcmp(name, "f32_plain")) return &g_sw.f32_plain;
+    return nullptr;
+}
 
 // MI355X: 256 compute units.  The planner is pure host arithmetic on purpose
 // (the workspace query must give the same answer with or without a GPU).
@@ -57,12 +79,10 @@ Plan make_plan(int B, int H, int n, int d, la_dtype dt)
         if (l < L) L = (int)l;
     }
     // tuning / test override: segment length in tokens
-    if (const char *e = std::getenv("LA_LSEG")) {
-        long v = std::atol(e);
-        if (v > 0 && scans <= 65535) {          // the segment scan's grid has one row per scan
-            v = round_up((int)(v > (1 << 30) ? (1 << 30) : v), p.tile);
-            L = (int)(v < round_up(n, p.tile) ? v : round_up(n, p.tile));
-        }
+    long v = g_sw.lseg.load(std::memory_order_relaxed);
+    if (v > 0 && scans <= 65535) {              // the segment scan's grid has one row per scan
+        v = round_up((int)(v > (1 << 30) ? (1 << 30) : v), p.tile);
+        L = (int)(v < round_up(n, p.tile) ? v : round_up(n, p.tile));
     }
     p.L = L;
     p.S = (n + L - 1) / L;
@@ -73,6 +93,7 @@ int check_common(int B, int H, int n, int d, la_dtype dt)
 {
     if (dt != LA_F32 && dt != LA_BF16) return LA_ERR_DTYPE;
     if (B < 1 || H < 1 || n < 1 || H > LA_MAX_HEADS) return LA_ERR_SHAPE;
+    if (n > LA_MAX_SEQ_LEN) return LA_ERR_SHAPE;        // keeps round_up(n, tile) and seg_lo + L in int
     if (d != 64 && d != 128) return LA_ERR_SHAPE;
     if ((long)B * H > (long)INT32_MAX / 4096) return LA_ERR_SHAPE;
     return LA_OK;
@@ -107,6 +128,8 @@ size_t state_bytes(const Plan &p, int B, int H, int d)
 }
 
 // ---- profiling hooks (single benchmarking thread) ---------------------------
+// The events are created by la_profile_enable, never inside a forward / backward call:
+// a call only records into events that already exist.
 struct Profile {
     bool on = false;
     int count = 0;
@@ -120,13 +143,8 @@ struct ScopedTimer {
     int slot = -1;
     explicit ScopedTimer(hipStream_t st) : s(st)
     {
-        if (!g_prof.on || g_prof.count >= LA_PROFILE_MAX_LAUNCHES) return;
+        if (!g_prof.on || g_prof.count >= g_prof.created) return;
         slot = g_prof.count++;
-        if (slot >= g_prof.created) {
-            if (hipEventCreate(&g_prof.start[slot]) != hipSuccess ||
-                hipEventCreate(&g_prof.stop[slot]) != hipSuccess) { slot = -1; g_prof.count--; return; }
-            g_prof.created = slot + 1;
-        }
         (void)hipEventRecord(g_prof.start[slot], s);
     }
     ~ScopedTimer() { if (slot >= 0) (void)hipEventRecord(g_prof.stop[slot], s); }
@@ -213,9 +231,9 @@ hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
         return d == 64 ? launch_bf16<64, REV, false>(a, lams, s) : launch_bf16<128, REV, false>(a, lams, s);
     }
     // fp32: d = 64 runs the literal FMA kernel with 64-row blocks; d = 128 the matrix-core kernel
-    // (32-row blocks; LA_F32_PLAIN selects the FMA kernel there too, for comparisons)
+    // (32-row blocks; the "f32_plain" switch selects the FMA kernel there too, for comparisons)
     if (d == 64) return launch_f32<64, 64, REV, STATE_ONLY>(a, lams, s);
-    if (std::getenv("LA_F32_PLAIN")) return launch_f32<128, 32, REV, STATE_ONLY>(a, lams, s);
+    if (g_sw.f32_plain.load(std::memory_order_relaxed)) return launch_f32<128, 32, REV, STATE_ONLY>(a, lams, s);
     return launch_f32m<128, REV, STATE_ONLY>(a, lams, s);
 }
 
@@ -251,8 +269,8 @@ ScanArgs make_args(const void *A, const void *Bm, const void *C, void *Out, cons
     // Decay cut-off: contributions weighted below 2^-bits of the nearest row's weight are
     // not read.  fp32: 2^-48, far below the 2^-24 resolution of the state they would be
     // added to; bf16: 2^-32, far below both that and the 2^-8 resolution of the bf16
-    // operand the state is rounded to when it is used (LA_NO_DECAY_SKIP reads everything).
-    a.skip_bits = std::getenv("LA_NO_DECAY_SKIP") ? 0.0f : (dt == LA_BF16 ? 32.0f : 48.0f);
+    // operand the state is rounded to when it is used (the "no_decay_skip" switch reads everything).
+    a.skip_bits = g_sw.no_decay_skip.load(std::memory_order_relaxed) ? 0.0f : (dt == LA_BF16 ? 32.0f : 48.0f);
     a.rev = 0;
     a.st_in = nullptr;
     a.st_out = nullptr;
@@ -350,7 +368,7 @@ int run_reverse_pair(const ScanArgs &ak, const ScanArgs &av, const LaLambdas &la
 {
     ScanLaunch l;
     l.items = (int)(scans * ak.S);
-    const bool pair = dt == LA_BF16 && std::getenv("LA_NO_PAIR") == nullptr;
+    const bool pair = dt == LA_BF16 && g_sw.no_pair.load(std::memory_order_relaxed) == 0;
     if (pair) {
         l.r[0] = ak; l.r[1] = av; l.nroles = 2;
         ScopedTimer t(s);
@@ -793,8 +811,33 @@ const char *la_strerror(int status)
 
 int la_profile_enable(int on)
 {
+    if (on) {
+        while (g_prof.created < LA_PROFILE_MAX_LAUNCHES) {
+            const int i = g_prof.created;
+            if (hipEventCreate(&g_prof.start[i]) != hipSuccess) return LA_ERR_LAUNCH;
+            if (hipEventCreate(&g_prof.stop[i]) != hipSuccess) {
+                (void)hipEventDestroy(g_prof.start[i]);
+                return LA_ERR_LAUNCH;
+            }
+            g_prof.created = i + 1;
+        }
+    }
     g_prof.on = on != 0;
     return LA_OK;
+}
+
+int la_debug_set(const char *name, long value)
+{
+    std::atomic<long> *sw = find_switch(name);
+    if (!sw) return LA_ERR_NULL;
+    sw->store(value, std::memory_order_relaxed);
+    return LA_OK;
+}
+
+long la_debug_get(const char *name)
+{
+    std::atomic<long> *sw = find_switch(name);
+    return sw ? sw->load(std::memory_order_relaxed) : -1;
 }
 
 int la_profile_collect(double *scan_kernel_ms, int *scan_kernel_launches)

@@ -112,13 +112,17 @@ struct ScanLaunch {
 };
 
 // Segment scan over local segment states, in place:
-//   forward: W[s] <- state entering segment s  (W[0] <- 0)
+//   forward: W[s] <- state entering segment s  (W[0] <- carried-in state or 0)
 //   reverse: W[s] <- state entering segment s from the right (W[S-1] <- 0)
 // Entering state of segment `seg` of scan `scan` (nullptr = zero).  Normally the
 // slot the segment scan wrote.  Heads whose decay over one whole segment is below
 // the pre-pass cut-off (lambda^L <= 2^-skip_bits) are "chain free": what entered the
 // previous segment no longer matters, the entering state IS the previous segment's
-// local state, and the segment scan leaves such heads alone.
+// local state, and the segment scan leaves their local states alone.  A state carried
+// in by the caller enters such a head's first segment through the last slot, which no
+// local state occupies (the final segment's is never produced): the segment scan copies
+// it there, so that no block-scan workgroup reads the caller's buffer while another one
+// may already be writing the state handed back into that same buffer.
 __device__ __forceinline__ const float *la_entering_state(const ScanArgs &a, int scan, int seg, bool rev,
                                                           float lg2_lambda, int dd)
 {
@@ -127,7 +131,7 @@ __device__ __forceinline__ const float *la_entering_state(const ScanArgs &a, int
     const float *slot0 = a.states + (size_t)scan * a.S * dd;
     const bool chain_free = a.skip_bits > 0.f && -lg2_lambda * (float)a.L >= a.skip_bits;
     if (!chain_free) return slot0 + (size_t)seg * dd;
-    if (!rev) return seg > 0 ? slot0 + (size_t)(seg - 1) * dd : (a.st_in ? a.st_in + (size_t)scan * dd : nullptr);
+    if (!rev) return seg > 0 ? slot0 + (size_t)(seg - 1) * dd : (a.st_in ? slot0 + (size_t)(a.S - 1) * dd : nullptr);
     return seg < a.S - 1 ? slot0 + (size_t)(seg + 1) * dd : nullptr;
 }
 

@@ -1,0 +1,32 @@
+/*
+ * Test and tuning switches of libla.so.  NOT part of the public interface (include/la.h):
+ * only the test-suite, the benchmark's A/B legs and tuning scripts call these.
+ *
+ * The switches are process-wide and all start at 0 (= the library's own choice).  The
+ * library never reads the environment, so la_workspace_bytes / la_plan and the launch that
+ * follows them always agree unless a switch is changed in between.  Do not change a switch
+ * while another thread is inside a library call.
+ *
+ *   "lseg"           > 0: segment length in tokens (rounded up to the tile length) instead
+ *                    of the planner's choice
+ *   "no_pair"        != 0: the dK and dV scans of the backward pass run as two launches
+ *                    instead of one XCD-paired launch
+ *   "no_decay_skip"  != 0: the segment-state pre-pass reads every block, also those whose
+ *                    decay weight is below its cut-off
+ *   "f32_plain"      != 0: fp32 at d = 128 runs the plain FMA kernel instead of the
+ *                    matrix-core one
+ *
+ * la_debug_set returns LA_OK, or LA_ERR_NULL for an unknown name; la_debug_get returns the
+ * value, or -1 for an unknown name.
+ */
+#ifndef LA_DEBUG_H
+#define LA_DEBUG_H
+#ifdef __cplusplus
+extern "C" {
+#endif
+int la_debug_set(const char *name, long value);
+long la_debug_get(const char *name);
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -50,7 +50,8 @@ __device__ __forceinline__ void lrpe_load8(const void *p, size_t idx, float (&x)
 __device__ __forceinline__ uint32_t lrpe_bf16_rne(float f)
 {
     uint32_t u = __float_as_uint(f);
-    u += 0x7fffu + ((u >> 16) & 1u);
+    if (f != f) return 0x7fc0u;                 // NaN stays a (quiet) NaN whatever its payload
+    u += 0x7fffu + ((u >> 16) & 1u);            // round to nearest even; overflow gives inf
     return u >> 16;
 }
 

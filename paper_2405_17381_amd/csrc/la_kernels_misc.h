@@ -16,10 +16,15 @@ __device__ __forceinline__ void segment_scan_body(const SegScanArgs &a, const La
     const int e = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (e >= a.DD) return;
     const float lam = lams.v[scan % a.H];
-    // chain-free heads (see la_entering_state) read their neighbour's local state directly
-    if (a.skip_bits > 0.f && -lams.lg2[scan % a.H] * (float)a.L >= a.skip_bits) return;
-    const float lamL = (float)pow((double)lam, (double)a.L);
     float *W = a.states + (size_t)scan * a.S * a.DD + e;
+    // chain-free heads (see la_entering_state) read their neighbour's local state directly;
+    // only a carried-in state is placed, in the slot no local state uses
+    if (a.skip_bits > 0.f && -lams.lg2[scan % a.H] * (float)a.L >= a.skip_bits) {
+        if (!REV && a.init)
+            *(float4 *)(W + (size_t)(a.S - 1) * a.DD) = *(const float4 *)(a.init + (size_t)scan * a.DD + e);
+        return;
+    }
+    const float lamL = (float)pow((double)lam, (double)a.L);
     float4 carry = make_float4(0.f, 0.f, 0.f, 0.f);
     if (!REV && a.init) carry = *(const float4 *)(a.init + (size_t)scan * a.DD + e);
     for (int i0 = 0; i0 < a.S; i0 += 8) {
@@ -106,6 +111,7 @@ __global__ __launch_bounds__(256) void la_decode_kernel(const void *q_, const vo
         if (BF16) {
             uint32_t u = __float_as_uint(s);
             u += 0x7fffu + ((u >> 16) & 1u);            // round to nearest even
+            if (s != s) u = 0x7fc00000u;                // NaN stays a (quiet) NaN whatever its payload
             ((uint16_t *)o_)[(size_t)scan * D + tid] = (uint16_t)(u >> 16);
         } else {
             ((float *)o_)[(size_t)scan * D + tid] = s;

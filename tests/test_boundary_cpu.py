@@ -32,8 +32,35 @@ def test_strerror_is_distinct_per_status():
     assert binding.la_strerror(-99) == "unknown status"
 
 
-def test_plan_and_workspace(monkeypatch):
-    monkeypatch.delenv("LA_LSEG", raising=False)
+@pytest.fixture(autouse=True)
+def _default_switches():
+    for name in ("lseg", "no_pair", "no_decay_skip", "f32_plain"):
+        binding.debug_set(name, 0)
+    yield
+    for name in ("lseg", "no_pair", "no_decay_skip", "f32_plain"):
+        binding.debug_set(name, 0)
+
+
+def test_debug_switches_are_exported_but_not_public(monkeypatch):
+    """The test / tuning switches live behind la_debug_set (csrc/la_debug.h), are absent from the
+    public header, and the environment is never read."""
+    lib = binding.load_library()
+    for name in binding.DEBUG_EXPORTS:
+        assert getattr(lib, name) is not None
+        assert name not in _declared_symbols()
+    assert binding.debug_get("lseg") == 0
+    binding.debug_set("lseg", 128)
+    assert binding.debug_get("lseg") == 128
+    with pytest.raises(binding.LaError):
+        binding.debug_set("no_such_switch", 1)
+    assert binding.debug_get("no_such_switch") == -1
+    binding.debug_set("lseg", 0)
+    base = binding.la_plan(1, 2, 3000, 64, binding.LA_BF16)
+    monkeypatch.setenv("LA_LSEG", "128")
+    assert binding.la_plan(1, 2, 3000, 64, binding.LA_BF16) == base
+
+
+def test_plan_and_workspace():
     # many scans: one segment, no scratch
     tile, L, S = binding.la_plan(32, 16, 2048, 128, binding.LA_BF16)
     assert (tile, S) == (64, 1) and L >= 2048
@@ -49,8 +76,8 @@ def test_plan_and_workspace(monkeypatch):
     assert binding.la_plan(1, 2, 256, 64, binding.LA_F32)[0] == 64
     assert binding.la_plan(1, 2, 256, 128, binding.LA_F32)[0] == 32
     # override
-    monkeypatch.setenv("LA_LSEG", "128")
-    assert binding.la_plan(1, 2, 300, 64, binding.LA_BF16) == (64, 128, 3)
+    with binding.debug(lseg=128):
+        assert binding.la_plan(1, 2, 300, 64, binding.LA_BF16) == (64, 128, 3)
     # invalid problem: no scratch, error status from the plan
     assert binding.la_workspace_bytes(1, 1, 16, 96, binding.LA_BF16, False) == 0
     with pytest.raises(binding.LaError):
@@ -63,13 +90,15 @@ def _raw_fwd(Q=4096, K=4096, V=4096, lam=(0.5,), O=4096, B=1, H=1, n=8, d=64, dt
     return lib.la_fwd(Q, K, V, lam_arr, O, B, H, n, d, dt, ws, wsb, None)
 
 
-def test_bad_arguments_are_rejected_without_a_gpu(monkeypatch):
+def test_bad_arguments_are_rejected_without_a_gpu():
     """Every rejection happens before any HIP call, so fake (never
     dereferenced) pointers are enough to drive the checks."""
-    monkeypatch.delenv("LA_LSEG", raising=False)
     assert _raw_fwd(d=96) == -2
     assert _raw_fwd(n=0) == -2
     assert _raw_fwd(H=257, lam=(0.5,) * 257) == -2
+    assert _raw_fwd(n=2 ** 31 - 1) == -2                        # beyond LA_MAX_SEQ_LEN
+    assert _raw_fwd(n=2 ** 31 - 100) == -2
+    assert binding.la_workspace_bytes(1, 1, 2 ** 31 - 1, 64, binding.LA_BF16, False) == 0
     assert _raw_fwd(dt=7) == -3
     assert _raw_fwd(Q=0) == -1
     assert _raw_fwd(lam=None) == -1
@@ -77,7 +106,7 @@ def test_bad_arguments_are_rejected_without_a_gpu(monkeypatch):
     for bad in (0.0, -0.1, 1.5, float("nan"), float("inf")):
         assert _raw_fwd(lam=(bad,)) == -4
     # segmented plan without scratch
-    monkeypatch.setenv("LA_LSEG", "64")
+    binding.debug_set("lseg", 64)
     assert _raw_fwd(n=256, ws=0, wsb=0) == -5
     assert _raw_fwd(n=256, ws=4096 + 8, wsb=1 << 30) == -5      # misaligned
     assert _raw_fwd(n=256, ws=4096, wsb=16) == -5               # too small
@@ -146,21 +175,16 @@ def test_inference_and_output_stage_entry_points_reject_bad_arguments():
     assert lib.la_fwd_strided(P, P, P, lam, P, ref(good), ref(odd), 1, 2, 8, 64, 1, 0, 0, None) == -7
     assert lib.la_bwd_strided(P, P, P, lam, P, P, P, P, ref(good), ref(good), ref(short), 1, 2, 8, 64, 1, 0, 0, None) == -2
     # la_bwd_saved: a segmented problem needs the forward workspace
-    import os
-    os.environ["LA_LSEG"] = "64"
-    try:
+    with binding.debug(lseg=64):
         assert lib.la_bwd_saved(P, P, P, lam, P, P, P, P, 0, 1, 1, 256, 64, 1, P, 1 << 30, None) == -5
         assert lib.la_bwd_saved(P, P, P, lam, P, P, P, P, P + 8, 1, 1, 256, 64, 1, P, 1 << 30, None) == -5
-    finally:
-        os.environ.pop("LA_LSEG", None)
 
 
-def test_planner_properties(monkeypatch):
+def test_planner_properties():
     """For any valid shape: the segment length is a multiple of the tile, the segments cover the
     sequence exactly, many scans are never cut, few scans are cut until two workgroups per compute
     unit exist (or the 512-token floor is reached), and the scratch query matches the plan."""
     import random
-    monkeypatch.delenv("LA_LSEG", raising=False)
     rng = random.Random(7)
     for _ in range(400):
         B = rng.choice([1, 2, 3, 8, 31, 64, 300])

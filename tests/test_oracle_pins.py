@@ -140,49 +140,36 @@ def test_finite_differences(impl):
             assert abs(fd - grad[idx]) <= 1e-7 * max(1.0, abs(grad[idx])), (which, idx)
 
 
-# ---- 7. block form == token form (Alg. 5 / Alg. 6, App. C) --------------------
-def _blocked_fwd(Q, K, V, lam, Bk):
-    """Alg. 5 restated for one scan, fp64, block length Bk (n % Bk == 0).
-    Lambda = diag(lam^1..lam^Bk) as in the algorithm box (the proof's
-    diag(1..lam^(Bk-1)) is a misprint: see test_block_form_rejects_misprint)."""
+# ---- 7. block form == token form (App. C's block identities) -------------------
+def _block_identities(Q, K, V, lam, dO, Bk, lambda_from_zero=False):
+    """The decomposition that Alg. 5 / Alg. 6 rest on (App. C), evaluated block by block with no
+    running update at all.  For the block of rows [t0, t1):
+      * the intra part is the oracle's quadratic form applied to the block alone;
+      * the state entering from the left and the one entering from the right are written
+        out as explicit weighted sums over the tokens outside the block,
+            KV  = sum_{s <  t0} lam^(t0-1-s) k_s v_s^T      (nearest earlier token: weight 1)
+            dKV = sum_{s >= t1} lam^(s-t1+1) q_s do_s^T     (nearest later token: weight lam);
+      * row r = 1..Bk of the block sees KV scaled by lam^r and dKV scaled by lam^(Bk-r).
+    `lambda_from_zero` swaps in the other printed variant of the row scale, lam^(r-1)."""
     n, d = Q.shape
+    pos = np.arange(n, dtype=np.float64)
     r = np.arange(1, Bk + 1, dtype=np.float64)
-    M = oracle.decay_matrix(Bk, lam)
-    Lam = lam ** r
-    LamInv = lam ** (Bk - r)            # lam^Bk * Lambda^-1, never via a division
-    KV = np.zeros((d, d))
-    O = np.zeros_like(Q)
-    for t in range(n // Bk):
-        sl = slice(t * Bk, (t + 1) * Bk)
-        Qt, Kt, Vt = Q[sl], K[sl], V[sl]
-        O[sl] = ((Qt @ Kt.T) * M) @ Vt + Lam[:, None] * (Qt @ KV)
-        KV = lam ** Bk * KV + (LamInv[:, None] * Kt).T @ Vt
-    return O
-
-
-def _blocked_bwd(Q, K, V, lam, dO, Bk):
-    """Alg. 6 restated for one scan, fp64."""
-    n, d = Q.shape
-    r = np.arange(1, Bk + 1, dtype=np.float64)
-    M = oracle.decay_matrix(Bk, lam)
-    Lam = lam ** r
-    LamInv = lam ** (Bk - r)
-    KV = np.zeros((d, d))
-    dKV = np.zeros((d, d))
-    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(Q), np.zeros_like(Q)
-    T = n // Bk
-    for t in range(T):
-        sl = slice(t * Bk, (t + 1) * Bk)
-        Kt, Vt, dOt = K[sl], V[sl], dO[sl]
-        dQ[sl] = ((dOt @ Vt.T) * M) @ Kt + Lam[:, None] * (dOt @ KV.T)
-        KV = lam ** Bk * KV + (LamInv[:, None] * Kt).T @ Vt
-    for t in range(T - 1, -1, -1):
-        sl = slice(t * Bk, (t + 1) * Bk)
-        Qt, Kt, Vt, dOt = Q[sl], K[sl], V[sl], dO[sl]
-        dK[sl] = ((dOt @ Vt.T) * M).T @ Qt + LamInv[:, None] * (Vt @ dKV.T)
-        dV[sl] = ((Qt @ Kt.T) * M).T @ dOt + LamInv[:, None] * (Kt @ dKV)
-        dKV = lam ** Bk * dKV + (Lam[:, None] * Qt).T @ dOt
-    return dQ, dK, dV
+    up = lam ** (r - 1 if lambda_from_zero else r)
+    down = lam ** (Bk - r)
+    O, dQ, dK, dV = (np.zeros_like(Q) for _ in range(4))
+    for t0 in range(0, n, Bk):
+        t1 = t0 + Bk
+        blk = slice(t0, t1)
+        q, k, v, g = (x[None, None, blk] for x in (Q, K, V, dO))
+        O_in = oracle.left_product_fwd(q, k, v, [lam])[0, 0]
+        dQ_in, dK_in, dV_in = (x[0, 0] for x in oracle.left_product_bwd(q, k, v, [lam], g))
+        KV = np.einsum("s,si,sj->ij", lam ** (t0 - 1 - pos[:t0]), K[:t0], V[:t0])
+        dKV = np.einsum("s,si,sj->ij", lam ** (pos[t1:] - t1 + 1), Q[t1:], dO[t1:])
+        O[blk] = O_in + up[:, None] * (Q[blk] @ KV)
+        dQ[blk] = dQ_in + up[:, None] * (dO[blk] @ KV.T)
+        dK[blk] = dK_in + down[:, None] * (V[blk] @ dKV.T)
+        dV[blk] = dV_in + down[:, None] * (K[blk] @ dKV)
+    return O, dQ, dK, dV
 
 
 @pytest.mark.parametrize("Bk", [1, 2, 4, 16])
@@ -190,12 +177,10 @@ def _blocked_bwd(Q, K, V, lam, dO, Bk):
 def test_block_form_equals_token_form(Bk, lam):
     n, d = 16, 4
     Q, K, V, dO = _rand(1, 1, n, d, seed=31)
-    O_ref = oracle.c_recurrence_fwd(Q, K, V, [lam])[0, 0]
-    g_ref = [x[0, 0] for x in oracle.c_recurrence_bwd(Q, K, V, [lam], dO)]
-    O_blk = _blocked_fwd(Q[0, 0], K[0, 0], V[0, 0], lam, Bk)
-    np.testing.assert_allclose(O_blk, O_ref, rtol=1e-11, atol=1e-12)
-    for x, r in zip(_blocked_bwd(Q[0, 0], K[0, 0], V[0, 0], lam, dO[0, 0], Bk), g_ref):
-        np.testing.assert_allclose(x, r, rtol=1e-11, atol=1e-12)
+    ref = [oracle.c_recurrence_fwd(Q, K, V, [lam])[0, 0]] + \
+        [x[0, 0] for x in oracle.c_recurrence_bwd(Q, K, V, [lam], dO)]
+    for x, want in zip(_block_identities(Q[0, 0], K[0, 0], V[0, 0], lam, dO[0, 0], Bk), ref):
+        np.testing.assert_allclose(x, want, rtol=1e-11, atol=1e-12)
 
 
 def test_block_form_rejects_misprint():
@@ -203,18 +188,11 @@ def test_block_form_rejects_misprint():
     longer matches the token form: the algorithm box's diag(lam, .., lam^Bk)
     is the reading to take."""
     n, d, Bk, lam = 16, 4, 4, 0.9
-    Q, K, V, _ = _rand(1, 1, n, d, seed=33)
+    Q, K, V, dO = _rand(1, 1, n, d, seed=33)
     ref = oracle.recurrence_fwd(Q, K, V, [lam])[0, 0]
-    M = oracle.decay_matrix(Bk, lam)
-    r = np.arange(1, Bk + 1, dtype=np.float64)
-    wrong = lam ** (r - 1)
-    KV = np.zeros((d, d))
-    O = np.zeros((n, d))
-    for t in range(n // Bk):
-        sl = slice(t * Bk, (t + 1) * Bk)
-        O[sl] = ((Q[0, 0, sl] @ K[0, 0, sl].T) * M) @ V[0, 0, sl] + wrong[:, None] * (Q[0, 0, sl] @ KV)
-        KV = lam ** Bk * KV + ((lam ** (Bk - r))[:, None] * K[0, 0, sl]).T @ V[0, 0, sl]
+    O, dQ, _, _ = _block_identities(Q[0, 0], K[0, 0], V[0, 0], lam, dO[0, 0], Bk, lambda_from_zero=True)
     assert np.max(np.abs(O - ref)) > 1e-2
+    assert np.max(np.abs(dQ - oracle.recurrence_bwd(Q, K, V, [lam], dO)[0][0, 0])) > 1e-2
 
 
 # ---- 8. causality --------------------------------------------------------------

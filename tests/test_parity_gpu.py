@@ -32,7 +32,7 @@ def _say(msg):
 def _need_gpu_and_clean_env(monkeypatch):
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     binding.load_library()                      # fail loudly if the HIP library is missing
-    monkeypatch.delenv("LA_LSEG", raising=False)
+    binding.debug_set("lseg", 0)
     yield
     torch.cuda.synchronize()
 
@@ -48,14 +48,14 @@ def _ref_inputs(xs, dtype):
 
 def _run_gpu(w, xs, lseg=None):
     if lseg is not None:
-        os.environ["LA_LSEG"] = str(lseg)
+        binding.debug_set("lseg", lseg)
     try:
         Q, K, V, dO = _to_dev(xs, w.dtype)
         O = binding.la_fwd(Q, K, V, w.lambdas)
         dQ, dK, dV = binding.la_bwd(Q, K, V, w.lambdas, dO)
         torch.cuda.synchronize()
     finally:
-        os.environ.pop("LA_LSEG", None)
+        binding.debug_set("lseg", 0)
     return [t.to(torch.float64).cpu().numpy() for t in (O, dQ, dK, dV)]
 
 
@@ -142,11 +142,11 @@ def test_decay_cutoff_of_the_prepass_is_invisible():
     w = synth.custom(1, len(lam), 8192, 128, lam, seed=99, dtype="bf16")
     xs = synth.draw(w)
     cut = _run_gpu(w, xs, lseg=2048)
-    os.environ["LA_NO_DECAY_SKIP"] = "1"
+    binding.debug_set("no_decay_skip", 1)
     try:
         full = _run_gpu(w, xs, lseg=2048)
     finally:
-        os.environ.pop("LA_NO_DECAY_SKIP", None)
+        binding.debug_set("no_decay_skip", 0)
     for a, b in zip(cut, full):
         assert oracle.rel_max_err(a, b) <= 1e-3
         assert np.mean(a != b) <= 1e-3          # flips are rare
@@ -158,18 +158,18 @@ def test_decay_cutoff_of_the_prepass_is_invisible():
 
 
 def test_fp32_matrix_core_kernel_against_the_plain_fma_kernel():
-    """d = 128 in fp32 runs on v_mfma_f32_32x32x2_f32; LA_F32_PLAIN selects the literal FMA kernel.
+    """d = 128 in fp32 runs on v_mfma_f32_32x32x2_f32; the "f32_plain" switch selects the literal FMA kernel.
     Two implementations of the same fp32 arithmetic: they differ by summation order only."""
     lam = [1.0, 0.999, 0.9, 0.3]
     w = synth.custom(2, 4, 777, 128, lam, seed=41, dtype="f32")
     xs = synth.draw(w)
     for lseg in (None, 256):
         mfma = _run_gpu(w, xs, lseg=lseg)
-        os.environ["LA_F32_PLAIN"] = "1"
+        binding.debug_set("f32_plain", 1)
         try:
             plain = _run_gpu(w, xs, lseg=lseg)
         finally:
-            os.environ.pop("LA_F32_PLAIN", None)
+            binding.debug_set("f32_plain", 0)
         for a, b in zip(mfma, plain):
             assert oracle.rel_max_err(a, b) <= 5e-6
             assert not np.array_equal(a, b)          # they really are different kernels
@@ -207,68 +207,91 @@ def test_outputs_are_fully_overwritten_and_neighbours_untouched():
 
 
 # ---- full-size configs, in the launch configuration the benchmark times -----------------
-def _sampled_case(w, sample, slabwise=False):
-    """Run the whole workload on the GPU; compare the complete scans of the
-    sampled (b, h) pairs with the oracle; check the trilinearity invariant
-    <dO,O> = <dQ,Q> = <dK,K> = <dV,V> over the entire tensors."""
+def _full_size_case(w, chunk, slabwise=False):
+    """Run the whole workload on the GPU into NaN-prefilled outputs and compare EVERY (b, h)
+    scan of O, dQ, dK, dV with the compiled oracle recurrence, `chunk` scans at a time (bounds
+    host memory).  Per output tensor the error is max|x - ref| / max|ref| over the whole tensor
+    (<= tol); per scan it is taken against that scan's own max|ref| (<= 2 tol, heads differ in
+    lambda).  The trilinearity invariant <dO,O> = <dQ,Q> = <dK,K> = <dV,V> is kept as a second,
+    oracle-free check over the entire tensors, bounded tightly enough that one wrong head fails it."""
     label = "%s B%d H%d n%d d%d" % (w.name, w.B, w.H, w.n, w.d)
-    _say("case %s (sampled scans %s)" % (label, sample))
+    tol = TOL[w.dtype]
+    _say("case %s (all %d scans, %d at a time)" % (label, w.B * w.H, chunk))
     t0 = time.time()
     dt = TDT[w.dtype]
     if slabwise:
         Q, K, V, dO = synth.draw_slabwise(w, device="cuda", dtype=dt)
-        host = None
     else:
-        host = synth.draw(w)
-        Q, K, V, dO = _to_dev(host, w.dtype)
+        Q, K, V, dO = _to_dev(synth.draw(w), w.dtype)
     _say("  inputs ready in %.1fs" % (time.time() - t0))
-    O = binding.la_fwd(Q, K, V, w.lambdas)
-    dQ, dK, dV = binding.la_bwd(Q, K, V, w.lambdas, dO)
+    outs = [torch.full_like(Q, float("nan")) for _ in range(4)]
+    binding.la_fwd(Q, K, V, w.lambdas, O=outs[0])
+    binding.la_bwd(Q, K, V, w.lambdas, dO, dQ=outs[1], dK=outs[2], dV=outs[3])
     torch.cuda.synchronize()
     _say("  plan (tile, L, S) = %s" % (binding.la_plan(w.B, w.H, w.n, w.d, binding.LA_BF16),))
-    for t in (O, dQ, dK, dV):
-        assert torch.isfinite(t.float()).all()
-    worst = 0.0
-    for (b, h) in sample:
-        ins = [x[b, h].to(torch.float64).cpu().numpy()[None, None] for x in (Q, K, V, dO)]
-        lam = [w.lambdas[h]]
+    names = ("O", "dQ", "dK", "dV")
+    for nm, t in zip(names, outs):
+        assert torch.isfinite(t.float()).all(), (label, nm, "unwritten or non-finite output")
+    scans = w.B * w.H
+    flat_in = [x.view(scans, w.n, w.d) for x in (Q, K, V, dO)]
+    flat_out = [x.view(scans, w.n, w.d) for x in outs]
+    max_diff = [0.0] * 4                       # whole-tensor max|x - ref| and max|ref|
+    max_ref = [0.0] * 4
+    worst_scan = [(0.0, -1)] * 4               # per-scan relative error and where
+    for lo in range(0, scans, chunk):
+        hi = min(scans, lo + chunk)
+        lam = [w.lambdas[s % w.H] for s in range(lo, hi)]
+        # a chunk goes to the oracle as one batch of hi - lo "heads", each with its own lambda
+        ins = [x[lo:hi].to(torch.float64).cpu().numpy()[None] for x in flat_in]
         ref = (oracle.c_recurrence_fwd(ins[0], ins[1], ins[2], lam),) + \
             oracle.c_recurrence_bwd(ins[0], ins[1], ins[2], lam, ins[3])
-        for nm, x, r in zip(("O", "dQ", "dK", "dV"), (O, dQ, dK, dV), ref):
-            got = x[b, h].to(torch.float64).cpu().numpy()[None, None]
-            err = oracle.rel_max_err(got, r)
-            worst = max(worst, err)
-            assert err <= TOL[w.dtype], (label, b, h, nm, err)
-        _say("  scan (b=%d,h=%d, lambda=%.6f) ok, worst so far %.3e  [%.1fs]"
-             % (b, h, w.lambdas[h], worst, time.time() - t0))
-    # trilinearity over everything, per head, accumulated in fp64 on the device.
-    # The inner products are sums of signed terms and can be small by
-    # cancellation, so the difference is measured against the sum of |terms|.
+        for j in range(4):
+            got = flat_out[j][lo:hi].to(torch.float64).cpu().numpy()[None]
+            diff = np.abs(got - ref[j]).max(axis=(0, 2, 3))
+            rmax = np.abs(ref[j]).max(axis=(0, 2, 3))
+            max_diff[j] = max(max_diff[j], float(diff.max()))
+            max_ref[j] = max(max_ref[j], float(rmax.max()))
+            per = diff / np.maximum(rmax, 1e-300)
+            k = int(per.argmax())
+            if per[k] > worst_scan[j][0]:
+                worst_scan[j] = (float(per[k]), lo + k)
+            assert per[k] <= 2 * tol, (label, names[j], "scan", lo + k, "b,h", divmod(lo + k, w.H), per[k])
+        if lo == 0 or hi == scans or (lo // chunk) % 8 == 0:
+            _say("  scans %d..%d compared  [%.1fs]" % (lo, hi - 1, time.time() - t0))
+    for j in range(4):
+        err = max_diff[j] / max_ref[j]
+        _say("  %-2s: rel err %.3e (tol %.0e); worst single scan %.3e at (b,h)=%s"
+             % (names[j], err, tol, worst_scan[j][0], divmod(worst_scan[j][1], w.H)))
+        assert err <= tol, (label, names[j], err)
+    # trilinearity over everything, per head, accumulated in fp64 on the device.  The inner
+    # products are sums of signed terms and can be small by cancellation, so the difference is
+    # measured against the sum of |terms|: correct results give <= 1e-5 there, a head whose
+    # gradient is noise of the right magnitude gives about 3e-4.
+    O, dQ, dK, dV = outs
+
     def inner(x, y):
         return (x.double() * y.double()).sum(dim=(0, 2, 3))
     base = inner(dO, O)
     scale = (dO.double() * O.double()).abs().sum(dim=(0, 2, 3)).clamp_min(1e-30)
     for nm, gx, x in (("dQ", dQ, Q), ("dK", dK, K), ("dV", dV, V)):
         rel = ((inner(gx, x) - base).abs() / scale).max().item()
-        assert rel <= 2e-2, (label, nm, rel)
         _say("  <%s,%s> vs <dO,O>: %.2e of sum|terms|" % (nm, nm[1:], rel))
-    _say("  trilinearity ok")
+        assert rel <= 5e-5, (label, nm, rel)
+    _say("  done in %.1fs" % (time.time() - t0))
 
 
 @pytest.mark.parametrize("n", [2048, 4096, 8192, 16384, 32768, 65536])
-def test_c3_sweep_point_sampled(n):
-    w = synth.workload("c3_%d" % n)
-    sample = [(0, 0), (w.B - 1, 15)] if n <= 16384 else [(0, 15)]
-    _sampled_case(w, sample)
+def test_c3_sweep_point_every_scan(n):
+    _full_size_case(synth.workload("c3_%d" % n), chunk=16)
 
 
-def test_c4_silu_features_sampled():
-    _sampled_case(synth.workload("c4"), [(0, 0), (7, 31), (3, 17)])
+def test_c4_silu_features_every_scan():
+    _full_size_case(synth.workload("c4"), chunk=16)
 
 
-def test_c5_long_context_sampled():
-    # heads with lambda = 1 (no decay over 2048 blocks) and the slowest decay
-    _sampled_case(synth.workload("c5"), [(0, 0), (0, 31)], slabwise=True)
+def test_c5_long_context_every_scan():
+    # 16 heads with lambda = 1 (no decay over 2048 blocks) and 16 slowly decaying ones
+    _full_size_case(synth.workload("c5"), chunk=4, slabwise=True)
 
 
 # ---- planner and limits --------------------------------------------------------------------
@@ -296,7 +319,7 @@ def test_hip_graph_capture_and_replay():
     into a HIP graph; every replay must reproduce the eager result bit for bit."""
     lam = [1.0, 0.999, 0.95, 0.7]
     w = synth.custom(2, 4, 1500, 128, lam, seed=11, dtype="bf16")
-    os.environ["LA_LSEG"] = "512"                 # pre-pass, segment scan and block scans
+    binding.debug_set("lseg", 512)                 # pre-pass, segment scan and block scans
     try:
         Q, K, V, dO = _to_dev(synth.draw(w), "bf16")
         need = binding.la_workspace_bytes(w.B, w.H, w.n, w.d, binding.LA_BF16, True)
@@ -337,7 +360,7 @@ def test_hip_graph_capture_and_replay():
         for o, r in zip(outs, replayed):
             assert torch.equal(o, r)
     finally:
-        os.environ.pop("LA_LSEG", None)
+        binding.debug_set("lseg", 0)
 
 
 @pytest.mark.parametrize("dtype,d,n,lseg", [("bf16", 128, 5000, None), ("bf16", 64, 1500, 256), ("f32", 128, 700, 128),
@@ -349,7 +372,7 @@ def test_backward_reusing_the_forward_states(dtype, d, n, lseg):
     w = synth.custom(1, 4, n, d, lam, seed=900 + n, dtype=dtype)
     xs = synth.draw(w)
     if lseg is not None:
-        os.environ["LA_LSEG"] = str(lseg)
+        binding.debug_set("lseg", lseg)
     try:
         Q, K, V, dO = _to_dev(xs, dtype)
         dt = binding.LA_BF16 if dtype == "bf16" else binding.LA_F32
@@ -361,7 +384,7 @@ def test_backward_reusing_the_forward_states(dtype, d, n, lseg):
         plain = binding.la_bwd(Q, K, V, w.lambdas, dO)
         torch.cuda.synchronize()
     finally:
-        os.environ.pop("LA_LSEG", None)
+        binding.debug_set("lseg", 0)
     assert torch.equal(fws, keep)                        # the forward workspace is only read
     q, k, v, g = _ref_inputs(xs, dtype)
     ref = oracle.c_recurrence_bwd(q, k, v, w.lambdas, g)

@@ -19,7 +19,7 @@ TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
 def _env(monkeypatch):
     assert torch.cuda.is_available()
     binding.load_library()
-    monkeypatch.delenv("LA_LSEG", raising=False)
+    binding.debug_set("lseg", 0)
     yield
     torch.cuda.synchronize()
 
@@ -33,7 +33,7 @@ def _case(dtype, d, n, pieces, lseg):
     q, k, v = [x.to(tdt).to(torch.float64).numpy() for x in host[:3]]
     O_ref, kv_ref = oracle.recurrence_fwd(q, k, v, lam, return_state=True)
     if lseg:
-        os.environ["LA_LSEG"] = str(lseg)
+        binding.debug_set("lseg", lseg)
     try:
         kv = torch.zeros(2, len(lam), d, d, dtype=torch.float32, device="cuda")
         outs, pos = [], 0
@@ -46,7 +46,7 @@ def _case(dtype, d, n, pieces, lseg):
         assert pos == n
         torch.cuda.synchronize()
     finally:
-        os.environ.pop("LA_LSEG", None)
+        binding.debug_set("lseg", 0)
     O = torch.cat(outs, dim=2).to(torch.float64).cpu().numpy()
     e_o = oracle.rel_max_err(O, O_ref)
     e_s = oracle.rel_max_err(kv.double().cpu().numpy(), kv_ref)

@@ -37,7 +37,7 @@ def test_strided_equals_contiguous(dtype, B, H, n, d, packed, lseg):
     Q, K, V, dO = _token_major(B, H, n, d, dtype, 7000 + n + d, packed)
     assert not Q.is_contiguous()
     if lseg is not None:
-        os.environ["LA_LSEG"] = str(lseg)
+        binding.debug_set("lseg", lseg)
     try:
         O = binding.la_fwd_strided(Q, K, V, lam)
         dQ, dK, dV = binding.la_bwd_strided(Q, K, V, lam, dO)
@@ -45,7 +45,7 @@ def test_strided_equals_contiguous(dtype, B, H, n, d, packed, lseg):
         dQc, dKc, dVc = binding.la_bwd(Q.contiguous(), K.contiguous(), V.contiguous(), lam, dO.contiguous())
         torch.cuda.synchronize()
     finally:
-        os.environ.pop("LA_LSEG", None)
+        binding.debug_set("lseg", 0)
     assert O.stride() == Q.stride()                      # outputs default to the inputs' layout
     for nm, a, b in (("O", O, Oc), ("dQ", dQ, dQc), ("dK", dK, dKc), ("dV", dV, dVc)):
         assert torch.equal(a.contiguous(), b), nm

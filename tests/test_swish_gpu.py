@@ -25,14 +25,14 @@ def _draw(B, H, n, d, dtype, seed):
 
 def _run(xs, lam, lseg):
     if lseg is not None:
-        os.environ["LA_LSEG"] = str(lseg)
+        binding.debug_set("lseg", lseg)
     try:
         Qp, Kp, V, dO = [x.cuda() for x in xs]
         O = binding.la_fwd_swish(Qp, Kp, V, lam)
         dQp, dKp, dV = binding.la_bwd_swish(Qp, Kp, V, lam, dO)
         torch.cuda.synchronize()
     finally:
-        os.environ.pop("LA_LSEG", None)
+        binding.debug_set("lseg", 0)
     return [t.to(torch.float64).cpu().numpy() for t in (O, dQp, dKp, dV)]
 
 

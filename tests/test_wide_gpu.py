@@ -25,14 +25,14 @@ def _draw(B, H, n, dk, dv, dtype, seed):
 
 def _run(xs, lam, lseg):
     if lseg is not None:
-        os.environ["LA_LSEG"] = str(lseg)
+        binding.debug_set("lseg", lseg)
     try:
         Qw, Kw, V, dO = [x.cuda() for x in xs]
         O = binding.la_fwd_wide(Qw, Kw, V, lam)
         dQw, dKw, dV = binding.la_bwd_wide(Qw, Kw, V, lam, dO)
         torch.cuda.synchronize()
     finally:
-        os.environ.pop("LA_LSEG", None)
+        binding.debug_set("lseg", 0)
     return [t.to(torch.float64).cpu().numpy() for t in (O, dQw, dKw, dV)]
 
 
