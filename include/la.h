@@ -67,7 +67,8 @@ typedef enum {
     LA_ERR_LAMBDA = -4,     /* a decay rate is not finite or not in (0, 1]      */
     LA_ERR_WORKSPACE = -5,  /* workspace NULL / misaligned / too small          */
     LA_ERR_LAUNCH = -6,     /* a HIP launch failed                              */
-    LA_ERR_ALIGN = -7       /* a tensor pointer is not 16-byte aligned          */
+    LA_ERR_ALIGN = -7,      /* a tensor pointer is not 16-byte aligned          */
+    LA_ERR_TOO_LARGE = -8   /* la_fwd_static: needs more than its static scratch */
 } la_status;
 
 /*
@@ -92,6 +93,29 @@ int la_fwd(const void *Q, const void *K, const void *V,
            void *O,
            int B, int H, int n, int d, la_dtype dt,
            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * la_fwd for callers that cannot allocate and have no workspace to give: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and
+ * bit-identical results, but the segment states live in a buffer of
+ * LA_STATIC_SCRATCH_BYTES that is part of the library's device image (one copy per GPU
+ * the library runs on, held until the process ends) instead of a caller workspace.  The
+ * call allocates nothing and calls no allocating routine; its first use on a device looks
+ * up that buffer's address (hipGetSymbolAddress), later calls reuse it.  The device the
+ * tensors and `hip_stream` belong to must be the current device.
+ * A problem for which la_workspace_bytes(B, H, n, d, dt, 0) exceeds
+ * LA_STATIC_SCRATCH_BYTES is refused with LA_ERR_TOO_LARGE and nothing is enqueued.
+ * (The planner cuts a problem into fewer than 768 (scan, segment) pieces of d*d*4 bytes
+ * each, so 64 MiB holds every plan it makes by itself, whatever B, H and n.)
+ * All calls on one GPU share that GPU's buffer: calls that may overlap in time on one GPU
+ * (different streams, different threads) race and must be serialised by the caller.
+ * Nothing in the buffer needs clearing between calls.
+ */
+#define LA_STATIC_SCRATCH_BYTES (64u << 20)
+int la_fwd_static(const void *Q, const void *K, const void *V,
+                  const float *lambda /* host, [H] */,
+                  void *O,
+                  int B, int H, int n, int d, la_dtype dt, void *hip_stream);
 
 /*
  * Backward pass (Alg. 6; Alg. 4 when lambda = 1): given dO = dLoss/dO,

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libla.so")
 EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_fwd_state", "la_decode_step", "la_gate_norm_fwd",
            "la_gate_norm_bwd", "la_fwd_swish", "la_bwd_swish", "la_fwd_wide", "la_bwd_wide", "la_lrpe_workspace_bytes",
            "la_lrpe_rotate_fwd", "la_lrpe_rotate_bwd", "la_fwd_strided", "la_bwd_strided", "la_bwd_saved", "la_strerror", "la_plan",
-           "la_profile_enable", "la_profile_collect")
+           "la_profile_enable", "la_profile_collect", "la_fwd_static")
 # exported for tests and tuning, declared in csrc/la_debug.h, not in include/la.h
 DEBUG_EXPORTS = ("la_debug_set", "la_debug_get")
 _lib = None
@@ -53,6 +53,8 @@ def load_library():
     lib.la_fwd.restype = ci
     lib.la_bwd.argtypes = [vp, vp, vp, fp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.la_bwd.restype = ci
+    lib.la_fwd_static.argtypes = [vp, vp, vp, fp, vp, ci, ci, ci, ci, ci, vp]
+    lib.la_fwd_static.restype = ci
     lib.la_debug_set.argtypes = [ctypes.c_char_p, ctypes.c_long]
     lib.la_debug_set.restype = ci
     lib.la_debug_get.argtypes = [ctypes.c_char_p]
@@ -170,6 +172,23 @@ def la_fwd(Q, K, V, lam, O=None, workspace: Optional[torch.Tensor] = None, _entr
                                              O.data_ptr(), B, H, n, d, dt, ws_ptr, ws_bytes, stream)
     if rc != 0:
         raise LaError(rc, _entry)
+    return O
+
+
+LA_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def la_fwd_static(Q, K, V, lam, O):
+    """la_fwd without a workspace: the library's static scratch holds the segment states.
+    O must be given (this wrapper allocates nothing either)."""
+    _check([Q, K, V, O])
+    B, H, n, d = Q.shape
+    with torch.cuda.device(Q.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_fwd_static(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _lam(lam, H),
+                                          O.data_ptr(), B, H, n, d, _dt(Q), stream)
+    if rc != 0:
+        raise LaError(rc, "la_fwd_static")
     return O
 
 

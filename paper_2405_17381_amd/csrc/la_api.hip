@@ -18,7 +18,31 @@
 #include "la_kernels_misc.h"
 #include "la_kernels_prepass.h"
 
+// Scratch of la_fwd_static: the segment states of one forward call.  One copy per GPU the
+// library runs on, held until the process ends.  In host code this name is only a handle
+// for hipGetSymbolAddress; the device address it yields is what the kernels are given.
+static __device__ __align__(256) unsigned char la_static_scratch[LA_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+// Device address of la_static_scratch on each GPU, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LA_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(la_static_scratch)) != hipSuccess || !ptr) return LA_ERR_LAUNCH;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return LA_OK;
+}
 
 // Test / tuning switches.  They are process-wide, start at zero, never look at the
 // environment and change only through la_debug_set (la_debug.h, not part of the public
@@ -577,6 +601,23 @@ int la_fwd(const void *Q, const void *K, const void *V, const float *lambda, voi
                    hip_stream, Variant());
 }
 
+int la_fwd_static(const void *Q, const void *K, const void *V, const float *lambda, void *O,
+                  int B, int H, int n, int d, la_dtype dt, void *hip_stream)
+{
+    int rc = check_common(B, H, n, d, dt);
+    if (rc != LA_OK) return rc;
+    const size_t need = state_bytes(make_plan(B, H, n, d, dt), B, H, d);
+    if (need > (size_t)LA_STATIC_SCRATCH_BYTES) return LA_ERR_TOO_LARGE;
+    void *scratch = nullptr;
+    if (need > 0) {
+        rc = static_scratch(&scratch);
+        if (rc != LA_OK) return rc;
+    }
+    // Every state slot that is read is written earlier in the same call (pre-pass, then
+    // segment scan), so what the previous call left in the scratch needs no clearing.
+    return forward(Q, K, V, lambda, O, nullptr, nullptr, B, H, n, d, dt, scratch, need, hip_stream, Variant());
+}
+
 int la_fwd_swish(const void *Qp, const void *Kp, const void *V, const float *lambda, void *O,
                  int B, int H, int n, int d, la_dtype dt,
                  void *workspace, size_t workspace_bytes, void *hip_stream)
@@ -805,6 +846,7 @@ const char *la_strerror(int status)
     case LA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case LA_ERR_LAUNCH: return "HIP kernel launch failed";
     case LA_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
+    case LA_ERR_TOO_LARGE: return "problem needs more scratch than the library's static buffer holds";
     default: return "unknown status";
     }
 }

@@ -27,8 +27,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_strerror_is_distinct_per_status():
-    msgs = {binding.la_strerror(s) for s in range(0, -8, -1)}
-    assert len(msgs) == 8
+    msgs = {binding.la_strerror(s) for s in range(0, -9, -1)}
+    assert len(msgs) == 9
     assert binding.la_strerror(-99) == "unknown status"
 
 
@@ -178,6 +178,18 @@ def test_inference_and_output_stage_entry_points_reject_bad_arguments():
     with binding.debug(lseg=64):
         assert lib.la_bwd_saved(P, P, P, lam, P, P, P, P, 0, 1, 1, 256, 64, 1, P, 1 << 30, None) == -5
         assert lib.la_bwd_saved(P, P, P, lam, P, P, P, P, P + 8, 1, 1, 256, 64, 1, P, 1 << 30, None) == -5
+    # la_fwd_static: a problem whose segment states exceed the static scratch is refused; bad
+    # arguments are refused as in la_fwd (all before any HIP call)
+    lam16 = (ctypes.c_float * 16)(*([0.9] * 16))
+    with binding.debug(lseg=512):
+        assert binding.la_workspace_bytes(2, 16, 131072, 128, 1, False) > binding.LA_STATIC_SCRATCH_BYTES
+        assert lib.la_fwd_static(P, P, P, lam16, P, 2, 16, 131072, 128, 1, None) == -8
+    # ... while every plan the library makes by itself fits
+    for (B, H, n) in ((2, 16, 131072), (1, 255, 10 ** 6), (5, 51, 2 * 10 ** 6), (1, 1, 2 ** 31 - 200)):
+        assert binding.la_workspace_bytes(B, H, n, 128, 1, False) <= binding.LA_STATIC_SCRATCH_BYTES
+    assert lib.la_fwd_static(P, P, P, lam, P, 1, 1, 8, 96, 1, None) == -2
+    assert lib.la_fwd_static(0, P, P, lam, P, 1, 1, 8, 64, 1, None) == -1
+    assert lib.la_fwd_static(P, P + 2, P, lam, P, 1, 1, 8, 64, 1, None) == -7
 
 
 def test_planner_properties():
