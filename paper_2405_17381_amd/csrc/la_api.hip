@@ -11,6 +11,7 @@
 #include "la_common.h"
 #include "la_debug.h"
 #include "la_kernels_bf16.h"
+#include "la_kernels_bf16_dma.h"
 #include "la_kernels_f32.h"
 #include "la_kernels_f32m.h"
 #include "la_kernels_gate.h"
@@ -52,6 +53,10 @@ struct Switches {
     std::atomic<long> no_pair{0};        // != 0: the dK and dV scans are launched separately
     std::atomic<long> no_decay_skip{0};  // != 0: the segment-state pre-pass reads every block
     std::atomic<long> f32_plain{0};      // != 0: fp32 at d = 128 runs the FMA kernel
+    std::atomic<long> store_policy{0};   // direct-to-LDS scan: 2 = ordinary instead of non-temporal result stores
+    std::atomic<long> ablate{0};         // 1..3: measurement-only variants of the direct-to-LDS scan
+    std::atomic<long> staged_scan{0};    // != 0: bf16 at d = 128 runs the register-staged block scan
+                                         // (64-row blocks) instead of the direct-to-LDS one (32-row)
 } g_sw;
 
 std::atomic<long> *find_switch(const char *name)
@@ -61,6 +66,9 @@ std::atomic<long> *find_switch(const char *name)
     if (!std::strcmp(name, "no_pair")) return &g_sw.no_pair;
     if (!std::strcmp(name, "no_decay_skip")) return &g_sw.no_decay_skip;
     if (!std::strcmp(name, "f32_plain")) return &g_sw.f32_plain;
+    if (!std::strcmp(name, "staged_scan")) return &g_sw.staged_scan;
+    if (!std::strcmp(name, "ablate")) return &g_sw.ablate;
+    if (!std::strcmp(name, "store_policy")) return &g_sw.store_policy;
     return nullptr;
 }
 
@@ -81,11 +89,16 @@ struct Plan {
     int S;          // segments per scan
 };
 
+// Block length of the block-scan kernel la_fwd / la_bwd run (the paper's "block size B").
 int tile_len(int d, la_dtype dt)
 {
-    if (dt == LA_BF16) return 64;
+    if (dt == LA_BF16) return (d == 128 && !g_sw.staged_scan.load(std::memory_order_relaxed)) ? 32 : 64;
     return d == 64 ? 64 : 32;
 }
+
+// Segment lengths are multiples of this: the longest block any kernel of the path uses
+// (the bf16 segment-state pre-pass and the extended scan variants work on 64-row blocks).
+int segment_granule(int d, la_dtype dt) { return dt == LA_BF16 ? 64 : tile_len(d, dt); }
 
 int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
@@ -93,20 +106,21 @@ Plan make_plan(int B, int H, int n, int d, la_dtype dt)
 {
     Plan p;
     p.tile = tile_len(d, dt);
+    const int gran = segment_granule(d, dt);
     const long scans = (long)B * H;
-    int L = round_up(n, p.tile);
+    int L = round_up(n, gran);
     if (scans < kComputeUnits) {
         const long want = (kTargetWorkgroups + scans - 1) / scans;   // segments wanted per scan
         long l = (n + want - 1) / want;
         if (l < kMinSegmentTokens) l = kMinSegmentTokens;
-        l = round_up((int)l, p.tile);
+        l = round_up((int)l, gran);
         if (l < L) L = (int)l;
     }
     // tuning / test override: segment length in tokens
     long v = g_sw.lseg.load(std::memory_order_relaxed);
     if (v > 0 && scans <= 65535) {              // the segment scan's grid has one row per scan
-        v = round_up((int)(v > (1 << 30) ? (1 << 30) : v), p.tile);
-        L = (int)(v < round_up(n, p.tile) ? v : round_up(n, p.tile));
+        v = round_up((int)(v > (1 << 30) ? (1 << 30) : v), gran);
+        L = (int)(v < round_up(n, gran) ? v : round_up(n, gran));
     }
     p.L = L;
     p.S = (n + L - 1) / L;
@@ -198,6 +212,42 @@ hipError_t launch_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s
     return hipGetLastError();
 }
 
+template <bool REV, bool NT_STORE, int ABL>
+hipError_t launch_bf16_dma_variant(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
+{
+    using Cfg = DmaCfg;
+    auto kern = la_scan_bf16_dma<REV, NT_STORE, ABL>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
+    if (attr_err != hipSuccess) return attr_err;
+    // paired launch: two workgroups per item, items padded to a multiple of the 8 XCDs
+    const unsigned wgs = a.nroles == 2 ? 2u * (unsigned)((a.items + 7) / 8 * 8) : (unsigned)a.items;
+    dim3 grid(wgs), block(Cfg::NT);
+    hipLaunchKernelGGL(kern, grid, block, Cfg::lds_bytes, s, a, lams);
+    return hipGetLastError();
+}
+
+// Cache policy of the result stores: non-temporal.  Timed alone, a single-scan launch is 8 %
+// faster with ordinary stores, but only because L2 then hands part of its write-back to
+// whatever runs next: over a forward + backward sequence non-temporal stores in all three
+// launches win by 6 % ("store_policy" switch = 2 selects ordinary stores, for measurements).
+template <bool REV>
+hipError_t launch_bf16_dma(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
+{
+    const bool nt = g_sw.store_policy.load(std::memory_order_relaxed) != 2;
+    switch (g_sw.ablate.load(std::memory_order_relaxed)) {
+    case 1: return launch_bf16_dma_variant<REV, true, 1>(a, lams, s);
+    case 2: return launch_bf16_dma_variant<REV, true, 2>(a, lams, s);
+    case 3: return launch_bf16_dma_variant<REV, true, 3>(a, lams, s);
+    case 4: return nt ? launch_bf16_dma_variant<REV, true, 4>(a, lams, s)
+                      : launch_bf16_dma_variant<REV, false, 4>(a, lams, s);
+    default: break;
+    }
+    return nt ? launch_bf16_dma_variant<REV, true, 0>(a, lams, s)
+              : launch_bf16_dma_variant<REV, false, 0>(a, lams, s);
+}
+
 template <int D, bool ACT>
 hipError_t launch_prepass_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
@@ -252,7 +302,9 @@ hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
             return d == 64 ? launch_prepass_bf16<64, false>(a, lams, s) : launch_prepass_bf16<128, false>(a, lams, s);
         }
         if (act) return d == 64 ? launch_bf16<64, REV, true>(a, lams, s) : launch_bf16<128, REV, true>(a, lams, s);
-        return d == 64 ? launch_bf16<64, REV, false>(a, lams, s) : launch_bf16<128, REV, false>(a, lams, s);
+        if (d == 64) return launch_bf16<64, REV, false>(a, lams, s);
+        if (g_sw.staged_scan.load(std::memory_order_relaxed)) return launch_bf16<128, REV, false>(a, lams, s);
+        return launch_bf16_dma<REV>(a, lams, s);
     }
     // fp32: d = 64 runs the literal FMA kernel with 64-row blocks; d = 128 the matrix-core kernel
     // (32-row blocks; the "f32_plain" switch selects the FMA kernel there too, for comparisons)

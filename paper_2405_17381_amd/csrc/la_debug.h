@@ -15,6 +15,13 @@
  *                    decay weight is below its cut-off
  *   "f32_plain"      != 0: fp32 at d = 128 runs the plain FMA kernel instead of the
  *                    matrix-core one
+ *   "ablate"         1..3: measurement-only variants of the direct-to-LDS block scan that
+ *                    leave work out (1: no result stores, 2: loads and barriers only,
+ *                    3: arithmetic only); their results are wrong by design
+ *   "store_policy"   2: the direct-to-LDS block scan stores its results with ordinary instead
+ *                    of non-temporal stores
+ *   "staged_scan"    != 0: bf16 at d = 128 runs the register-staged block scan (64-row
+ *                    blocks) instead of the direct-to-LDS one (32-row blocks)
  *
  * la_debug_set returns LA_OK, or LA_ERR_NULL for an unknown name; la_debug_get returns the
  * value, or -1 for an unknown name.

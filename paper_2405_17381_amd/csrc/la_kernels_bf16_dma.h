@@ -1,0 +1,429 @@
+// bf16 block scan for d = 128 fed by global -> LDS direct loads (gfx950).
+//
+// Same arithmetic as la_scan_bf16 (the block loop of Alg. 5 / Alg. 6: masked intra-block
+// left product, inter-block right product against the running state, state update), same
+// ownership (wave w owns value features [32w, 32w+32) of Out and of the state, which never
+// leaves its accumulator registers), but the tiles take another road into the compute
+// units, chosen so that more bytes are in flight per workgroup at no cost in registers:
+//
+//   * 32-row blocks.  A block's three tiles (A, Bm, C: 3 x 8 KB) are written into LDS by
+//     global_load_lds_dwordx4, row-major and untouched, into one of three stages: the loads
+//     of the next TWO blocks are outstanding while a block is computed, they occupy no
+//     VGPRs and nobody executes a staging pass.
+//   * Nothing is transposed or permuted on the way in.  Operands contracted over the
+//     feature dim (scores, inter) are read as rows with ds_read_b128; operands contracted
+//     over the token dim (C^T for the intra product, Bm^T and C for the state update) are
+//     read from the same row-major tiles with the transposing ds_read_b64_tr_b16.
+//   * The state feeds the inter product straight from the accumulators as before; instead
+//     of storing the A tile with permuted columns, the two lane halves exchange the rows
+//     of the state operand they lack with v_permlane32_swap.
+//   * The masked scores P never touch LDS: every wave computes the whole 32 x 32 score
+//     tile itself (8 MFMAs), and the accumulator layout of S^T is already the operand
+//     layout of P^T, with the keys in the order (4g..4g+3, 8+4g..8+4g+3 per 16) that the
+//     transposing reads of C^T are made to follow.
+//   * The decay weights of the state update go onto the C fragments of the wave's own
+//     slice (two fragments per block) rather than onto the whole Bm tile.
+//   * Two barriers per block.  The four waves put their 32-feature slices of the Out tile
+//     side by side in an 8 KB LDS area; after the second barrier each wave writes 8 whole
+//     rows to memory, 1 KB contiguous per store instruction.  (Measured on the kernel's
+//     load / store skeleton: whole rows instead of 64-byte pieces per wave are worth 5 to
+//     10 %.)
+//
+// LDS tile layout: row r (0..31) at byte 256 r; its sixteen 16-byte chunks are stored at
+// chunk position c ^ sw(r), sw(r) = the low four bits of r rotated left by one.  A direct
+// load writes 64 lanes x 16 bytes to consecutive LDS addresses (4 rows); the swizzle is
+// applied on the global side, lane -> chunk (lane & 15) ^ sw(row).  With it the 16 lanes
+// of a ds_read_b128 group (16 rows, one chunk) and the 16 lanes of a transposing read
+// (4 rows x 32 bytes) each cover all banks exactly once.
+//
+// ds_read_b64_tr_b16, as measured: in each group of 16 lanes, lane i receives, as its four
+// 16-bit elements e = 0..3, element i % 4 of the 8 bytes that lane i / 4 + 4 e of the group
+// points at.  With lane (a + 4 b) pointing at row b, columns 4a..4a+3, lane i ends up with
+// column i of rows 0..3: a column-major fragment out of a row-major tile.
+//
+// The direct loads are issued from inline assembly and waited for by hand (s_waitcnt
+// vmcnt(N), N = the 6 loads of the one block that may stay in flight plus the 2 stores of
+// the block just finished), and the workgroup
+// barrier is the bare s_barrier behind an LDS-only wait: the compiler, when it sees such a
+// load, waits for ALL of them before the next transposing LDS read or fenced barrier, which
+// would leave no prefetch at all.  Vector-memory instructions complete in issue order, so
+// "at most the N youngest outstanding" means that everything older has landed; for that
+// count to be exact every wave always issues both of its store instructions (rows past the
+// end of the sequence re-store the last real row with the same data).
+#pragma once
+#include "la_kernels_bf16.h"
+
+typedef __attribute__((address_space(3))) void la_lds_void;
+typedef short la_s4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) la_s4 la_lds_s4;
+
+struct DmaCfg {
+    static constexpr int D = 128, BK = 32;
+    static constexpr int NS = 3;                             // stages: NS - 1 blocks of prefetch
+    static constexpr int NW = 4, NT = 64 * NW;
+    static constexpr int NTILE = 3;                          // tiles per stage: A, Bm, C
+    static constexpr int TILE_BYTES = BK * D * 2;            // 8192
+    static constexpr int STAGE_BYTES = NTILE * TILE_BYTES;
+    static constexpr int SO_BYTES = BK * D * 2;              // the Out tile, bf16
+    static constexpr size_t lds_bytes = (size_t)NS * STAGE_BYTES + SO_BYTES;   // 81920
+};
+
+__device__ __forceinline__ int dma_sw(int r) { return ((r << 1) | ((r >> 3) & 1)) & 15; }
+
+#define LA_WAIT_VM(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
+template <int N>
+__device__ __forceinline__ void la_wait_vm()
+{
+    static_assert(N == 0 || N == 4 || N == 6 || N == 8 || N == 10 || N == 12, "add the count");
+    if (N == 0) LA_WAIT_VM(0);
+    if (N == 4) LA_WAIT_VM(4);
+    if (N == 6) LA_WAIT_VM(6);
+    if (N == 8) LA_WAIT_VM(8);
+    if (N == 10) LA_WAIT_VM(10);
+    if (N == 12) LA_WAIT_VM(12);
+}
+// LDS traffic of this wave complete, then the workgroup barrier; nothing moves across it
+#define LA_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+
+// One global -> LDS load of 16 bytes per lane: lane l's bytes land at lds_addr + 16 l
+// (lds_addr wave-uniform, in M0).  NT: the non-temporal hint.
+template <bool NT>
+__device__ __forceinline__ void dma_load16(const void *gptr, uint32_t lds_addr)
+{
+    if (NT)
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off nt" ::"v"(gptr), "s"(lds_addr) : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory", "m0");
+}
+
+__device__ __forceinline__ U2 lds_read_tr(const unsigned char *p)
+{
+    const la_s4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((la_lds_s4 *)p);
+    return __builtin_bit_cast(U2, v);
+}
+
+// ABL != 0 builds measurement-only variants that leave parts of the work out (their results
+// are wrong by design; reached only through the "ablate" debug switch):
+//   1: no result stores   2: loads, waits and barriers only (no arithmetic, no stores)
+//   3: arithmetic only (no loads, no stores; computes on whatever the LDS holds)
+//   4: loads, barriers and result stores, no arithmetic (stores whatever the LDS area holds)
+// NT_STORE: the result stores carry the non-temporal hint (a template parameter because
+// two stores that differ only in the hint are merged into one plain store when they sit in
+// the two arms of a run-time branch).
+template <bool REV, bool NT_STORE, int ABL>
+__global__ __launch_bounds__(256, 2) void la_scan_bf16_dma(ScanLaunch launch, LaLambdas lams)
+{
+    using Cfg = DmaCfg;
+    constexpr int D = Cfg::D, BK = Cfg::BK, NS = Cfg::NS, NTILE = Cfg::NTILE;
+    constexpr int KS_D = D / 16;               // k-steps over the feature dim (8)
+    constexpr int KS_B = BK / 16;              // k-steps over the block rows (2)
+    constexpr int MT_D = D / 32;               // 32-row tiles over the feature dim (4)
+    constexpr int SPW = 8 / Cfg::NW;           // 4-row load slots per wave and tile (8 slots per tile)
+    constexpr int LOADS = NTILE * SPW;         // direct loads per wave and block
+
+    extern __shared__ __align__(16) unsigned char smem_dma[];
+
+    const int tid = threadIdx.x;
+    const int l = tid & 63, l32 = l & 31, g = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index = value-feature slice, in a scalar register
+
+    int item = blockIdx.x, role = 0;
+    if (launch.nroles == 2) {
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        role = slot & 1;
+        item = (slot >> 1) * 8 + xcd;
+        if (item >= launch.items) return;
+    }
+    const ScanArgs &a = launch.r[role];
+    const int seg = item % a.S;
+    const int scan = item / a.S;
+    const float lg = lams.lg2[scan % a.H];
+    auto pw = [lg](int k) -> float { return exp2f((float)k * lg); };
+
+    const int seg_lo = seg * a.L;
+    const int seg_hi = min(a.n, seg_lo + a.L);
+    const int nblk = (seg_hi - seg_lo + BK - 1) / BK;
+
+    const size_t base = (size_t)scan * a.n * D;
+    // tiles of a stage, in LDS order: A, Bm, C
+    const uint16_t *gT[NTILE];
+    gT[0] = (const uint16_t *)a.A + base;
+    gT[1] = (const uint16_t *)a.Bm + base;
+    gT[2] = (const uint16_t *)a.C + base;
+    uint16_t *gO = (uint16_t *)a.Out + base;
+
+    // ---- per-lane constants ----------------------------------------------------------
+    // key / token held in slot e (0..7) of k-step ks: 16 ks + (e < 4 ? 4g + e : 8 + 4g + e - 4);
+    // the same order as accumulator register v = 8 ks + e of a 32 x 32 tile (row 8 (v/4) + 4g + v%4)
+    float mk[16];                              // decay mask of the score tile: lane = q, register = key
+    float wt[16];                              // state-update weight of the token in slot (ks, e)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int key = 8 * (v >> 2) + 4 * g + (v & 3);
+        const int dist = REV ? (key - l32) : (l32 - key);
+        mk[v] = dist >= 0 ? pw(dist) : 0.0f;
+        wt[v] = REV ? pw(key) : pw(BK - 1 - key);
+    }
+    const float rsq = REV ? pw(BK - l32) : pw(l32 + 1);          // inter-block scale of column q = l32
+    float lamBK = pw(BK);
+    const bool want_final = !REV && a.st_out != nullptr && seg == a.S - 1;
+
+    // row-operand reads: row l32, chunk 2 ks + g
+    const int ro_base = l32 * 256;
+    const int ro_sw = dma_sw(l32) ^ g;                           // chunk position = (2 ks) ^ ro_sw
+    // transposing reads: lane = (a4 + 4 b4) + 16 h16 + 32 g
+    const int a4 = l & 3, b4 = (l >> 2) & 3, h16 = (l >> 4) & 1;
+    const int tr_base = (4 * g + b4) * 256 + 8 * (a4 & 1);       // row 4g + b4, 8-byte half of the chunk
+    const int tr_sw = (2 * h16 + (a4 >> 1)) ^ (8 * g + 2 * b4);  // chunk within the 32 columns ^ sw(row), sel = 0
+    // direct loads: load slot ii = SPW w + j covers tile rows 4 ii .. 4 ii + 3
+    int dma_row[SPW], dma_col[SPW];
+#pragma unroll
+    for (int j = 0; j < SPW; ++j) {
+        dma_row[j] = 4 * (SPW * w + j) + (l >> 4);
+        dma_col[j] = 8 * ((l & 15) ^ dma_sw(dma_row[j]));        // element offset of the chunk fetched
+    }
+    // Out tile: row q at 256 q, chunk c (8 features) at position c ^ (q & 15)
+    unsigned char *sO = smem_dma + NS * Cfg::STAGE_BYTES;
+    // LDS byte address of the first stage, as the direct loads want it (wave-uniform)
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(la_lds_void *)smem_dma);
+
+    // ---- running state: St[i][j], j in this wave's slice ------------------------------
+    f32x16_t st[MT_D];
+    const float *gSt = la_entering_state(a, scan, seg, REV, lg, D * D);
+    const bool has_init = gSt != nullptr;
+    if (has_init && a.transpose_init) {
+        // the stored state is that of the scan with Bm and C exchanged: through LDS, transposed
+        float *sT = reinterpret_cast<float *>(smem_dma);         // [D][D+1]
+        for (int e = tid * 4; e < D * D; e += 4 * Cfg::NT) {
+            const float4 x = *(const float4 *)(gSt + e);
+            float *q = sT + (e / D) * (D + 1) + (e % D);
+            q[0] = x.x; q[1] = x.y; q[2] = x.z; q[3] = x.w;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int mt = 0; mt < MT_D; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
+                st[mt][v] = sT[(32 * w + l32) * (D + 1) + i];
+            }
+        __syncthreads();
+    } else {
+#pragma unroll
+        for (int mt = 0; mt < MT_D; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
+                st[mt][v] = has_init ? gSt[(size_t)i * D + 32 * w + l32] : 0.0f;
+            }
+    }
+
+    // ---- global -> LDS loads of one block ------------------------------------------------
+    // Rows past the segment end fetch the segment's last row (always in bounds) and are
+    // zeroed in LDS by the lane that fetched them once the load has landed.
+    // Tiles that no other workgroup reads carry the non-temporal hint: everything in a
+    // single-scan launch, the A operand in a paired launch.
+    const bool nt_all = launch.nroles == 1;
+    const auto blk_of = [&](int ib) { return REV ? (nblk - 1 - ib) : ib; };
+    auto issue = [&](int ib, int stage) {
+        if (ABL == 3) return;
+        const int t0 = seg_lo + blk_of(ib) * BK;
+#pragma unroll
+        for (int j = 0; j < SPW; ++j) {
+            const size_t off = (size_t)min(t0 + dma_row[j], seg_hi - 1) * D + dma_col[j];
+            const uint32_t dst = lds0 + stage * Cfg::STAGE_BYTES + (SPW * w + j) * 1024;   // lane l lands at + 16 l
+            dma_load16<true>(gT[0] + off, dst);
+            if (nt_all) {
+#pragma unroll
+                for (int t = 1; t < NTILE; ++t) dma_load16<true>(gT[t] + off, dst + t * Cfg::TILE_BYTES);
+            } else {
+#pragma unroll
+                for (int t = 1; t < NTILE; ++t) dma_load16<false>(gT[t] + off, dst + t * Cfg::TILE_BYTES);
+            }
+        }
+    };
+    // ---- Out tile: LDS -> memory, 8 whole rows per wave.  Always two store instructions
+    // with every lane active (see the note on counting above): a row past the end of the
+    // sequence stores the last real row again.
+    auto store_out = [&](int t0) {
+        if (ABL != 0 && ABL != 4) return;
+        const int last = min(BK, seg_hi - t0) - 1;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int row = min(8 * w + 4 * p + (l >> 4), last), ch = l & 15;
+            const U4 o = *(const U4 *)(sO + row * 256 + ((ch ^ (row & 15)) << 4));
+            U4 *dst = (U4 *)(gO + (size_t)(t0 + row) * D + 8 * ch);
+            if (NT_STORE) __builtin_nontemporal_store(o, dst);
+            else *dst = o;
+        }
+    };
+
+    constexpr int PF = NS - 1;                 // blocks of prefetch
+#pragma unroll
+    for (int i = 0; i < PF; ++i)
+        if (i < nblk) issue(i, i);
+    constexpr int ST = (ABL == 0 || ABL == 4) ? 2 : 0;           // store instructions per wave and block
+
+    int stage = 0;
+    for (int ib = 0; ib < nblk; ++ib) {
+        const int t0 = seg_lo + blk_of(ib) * BK;
+        unsigned char *sb = smem_dma + stage * Cfg::STAGE_BYTES;
+        // Every iteration issues the loads of block ib + PF, then (at its end) the 2 stores of
+        // block ib.  Counting back from the youngest instruction, what may still be outstanding
+        // when block ib must have landed is PF - 1 times (stores, loads): the loads of blocks
+        // ib + 1 .. ib + PF - 1 with the stores between them.  At the start the loads of the
+        // first PF blocks were issued back to back (fewer stores in between), near the end
+        // some loads were never issued; short segments simply wait for everything.
+        if (nblk < 2 * PF + 1 || ib + 1 >= nblk) {
+            la_wait_vm<0>();
+        } else if constexpr (PF == 2) {
+            if (ib == 0) la_wait_vm<LOADS>();
+            else la_wait_vm<LOADS + ST>();
+        } else {                                // PF == 3
+            if (ib == 0) la_wait_vm<2 * LOADS>();
+            else if (ib == 1) la_wait_vm<2 * LOADS + ST>();
+            else if (ib + 2 < nblk) la_wait_vm<2 * (LOADS + ST)>();
+            else la_wait_vm<LOADS + ST>();      // ib == nblk - 2: the loads of one block are younger
+        }
+        if (t0 + BK > seg_hi) {                 // partial block: zero padding (exact)
+            const U4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int j = 0; j < SPW; ++j)
+                if (t0 + dma_row[j] >= seg_hi) {
+                    unsigned char *dst = sb + (SPW * w + j) * 1024 + 16 * l;
+#pragma unroll
+                    for (int t = 0; t < NTILE; ++t) *(U4 *)(dst + t * Cfg::TILE_BYTES) = z;
+                }
+            if (want_final) {
+                // The state handed back must be the one after the last real token: weight
+                // row r of the m real rows by lambda^(m-1-r) and decay the old state by
+                // lambda^m instead of padding the block out to BK rows.
+                const int m = seg_hi - t0;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) wt[v] = pw(max(m - 1 - (8 * (v >> 2) + 4 * g + (v & 3)), 0));
+                lamBK = pw(m);
+            }
+        }
+        LA_LDS_BARRIER();                       // the block has landed for every wave; the stage
+                                                // of block ib - 1 is free for block ib + PF
+        if (ib + PF < nblk) issue(ib + PF, stage >= 1 ? stage - 1 : NS - 1);
+
+        if (ABL == 2 || ABL == 4) {
+            if (ABL == 4) {
+                LA_LDS_BARRIER();
+                store_out(t0);
+            }
+            stage = stage + 1 < NS ? stage + 1 : 0;
+            continue;
+        }
+        const unsigned char *sA = sb, *sB = sb + Cfg::TILE_BYTES, *sC = sb + 2 * Cfg::TILE_BYTES;
+
+        // ---- row fragments of A (both products) and of Bm (scores) ---------------------
+        U4 fa[KS_D];
+#pragma unroll
+        for (int ks = 0; ks < KS_D; ++ks) fa[ks] = *(const U4 *)(sA + ro_base + (((2 * ks) ^ ro_sw) << 4));
+        // ---- scores: S^T = Bm A^T (lane = q, registers = keys), in two halves of the k range
+        f32x16_t s = {0};
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            U4 fb[KS_D / 2];
+#pragma unroll
+            for (int k = 0; k < KS_D / 2; ++k)
+                fb[k] = *(const U4 *)(sB + ro_base + (((2 * (4 * h + k)) ^ ro_sw) << 4));
+            LA_BATCH_FENCE();
+#pragma unroll
+            for (int k = 0; k < KS_D / 2; ++k) s = mfma32(fb[k], fa[4 * h + k], s);
+        }
+        // ---- inter block: x^T = St^T A^T; the state operand is made from the accumulators:
+        // lane half g holds rows 4g..4g+3 and 8+4g..8+4g+3 of every 16, the operand wants
+        // rows 8g..8g+7: the halves exchange what they lack.
+        f32x16_t x = {0};
+#pragma unroll
+        for (int ks = 0; ks < KS_D; ++ks) {
+            const int mt = ks >> 1, h8 = 8 * (ks & 1);
+            const uint32_t x0 = pack2_bf16(st[mt][h8 + 0], st[mt][h8 + 1]);
+            const uint32_t x1 = pack2_bf16(st[mt][h8 + 2], st[mt][h8 + 3]);
+            const uint32_t y0 = pack2_bf16(st[mt][h8 + 4], st[mt][h8 + 5]);
+            const uint32_t y1 = pack2_bf16(st[mt][h8 + 6], st[mt][h8 + 7]);
+            const auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+            const auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+            const U4 so = {s0[0], s1[0], s0[1], s1[1]};
+            x = mfma32(so, fa[ks], x);
+        }
+        // ---- C^T fragments of this wave's slice (transposing reads), plain and weighted ---
+        U4 cf[KS_B], cw[KS_B];
+#pragma unroll
+        for (int ks = 0; ks < KS_B; ++ks) {
+            const unsigned char *p = sC + tr_base + 16 * ks * 256;
+            const U2 lo = lds_read_tr(p + ((((4 * w) ^ tr_sw)) << 4));
+            const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * w) ^ tr_sw ^ 1)) << 4));
+            cf[ks] = U4{lo[0], lo[1], hi[0], hi[1]};
+        }
+        // ---- P = bf16(S * mask) stays in registers: it is already the operand of the intra product
+        U4 pk[KS_B];
+#pragma unroll
+        for (int ks = 0; ks < KS_B; ++ks)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                pk[ks][e] = pack2_bf16(s[8 * ks + 2 * e] * mk[8 * ks + 2 * e],
+                                       s[8 * ks + 2 * e + 1] * mk[8 * ks + 2 * e + 1]);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) x[v] *= rsq;
+        // ---- intra block: Out^T += C^T P^T
+#pragma unroll
+        for (int ks = 0; ks < KS_B; ++ks) x = mfma32(cf[ks], pk[ks], x);
+        // ---- Out tile -> LDS (bf16): lane holds 4 consecutive features per v4
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+            U2 o;
+            o[0] = pack2_bf16(x[4 * v4 + 0], x[4 * v4 + 1]);
+            o[1] = pack2_bf16(x[4 * v4 + 2], x[4 * v4 + 3]);
+            *(U2 *)(sO + l32 * 256 + (((4 * w + v4) ^ (l32 & 15)) << 4) + 8 * g) = o;
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS_B; ++ks)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                cw[ks][e] = pack2_bf16(bf16_lo(cf[ks][e]) * wt[8 * ks + 2 * e],
+                                       bf16_hi(cf[ks][e]) * wt[8 * ks + 2 * e + 1]);
+        // ---- state update: St = lambda^BK St + Bm^T (w C) -----------------------------------
+#pragma unroll
+        for (int mt = 0; mt < MT_D; ++mt) {
+            U4 bt[KS_B];
+#pragma unroll
+            for (int ks = 0; ks < KS_B; ++ks) {
+                const unsigned char *p = sB + tr_base + 16 * ks * 256;
+                const U2 lo = lds_read_tr(p + ((((4 * mt) ^ tr_sw)) << 4));
+                const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * mt) ^ tr_sw ^ 1)) << 4));
+                bt[ks] = U4{lo[0], lo[1], hi[0], hi[1]};
+            }
+            LA_BATCH_FENCE();
+            f32x16_t u = st[mt];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) u[v] *= lamBK;
+#pragma unroll
+            for (int ks = 0; ks < KS_B; ++ks) u = mfma32(bt[ks], cw[ks], u);
+            st[mt] = u;
+        }
+        LA_LDS_BARRIER();                       // the Out tile is complete
+        store_out(t0);
+        stage = stage + 1 < NS ? stage + 1 : 0;
+    }
+    if (ABL != 0) {                             // keep the arithmetic alive: one store per wave
+        float keep = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < MT_D; ++mt) keep += st[mt][0];
+        if (l == 0) gO[(size_t)seg_lo * D + 32 * w] = (uint16_t)(__float_as_uint(keep + (float)sO[l]) >> 16);
+    }
+
+    if (want_final) {
+        float *dst = a.st_out + (size_t)scan * (D * D);
+#pragma unroll
+        for (int mt = 0; mt < MT_D; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
+                dst[(size_t)i * D + 32 * w + l32] = st[mt][v];
+            }
+    }
+}

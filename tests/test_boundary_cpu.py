@@ -63,7 +63,7 @@ def test_debug_switches_are_exported_but_not_public(monkeypatch):
 def test_plan_and_workspace():
     # many scans: one segment, no scratch
     tile, L, S = binding.la_plan(32, 16, 2048, 128, binding.LA_BF16)
-    assert (tile, S) == (64, 1) and L >= 2048
+    assert (tile, S) == (32, 1) and L >= 2048
     assert binding.la_workspace_bytes(32, 16, 2048, 128, binding.LA_BF16, False) == 0
     # few scans, long sequence: segmented, scratch = scans * S * d*d * 4
     tile, L, S = binding.la_plan(1, 16, 65536, 128, binding.LA_BF16)

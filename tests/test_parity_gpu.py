@@ -405,3 +405,27 @@ def test_very_long_sequence_many_segments():
     assert S > 200 and n % L != 0
     _say("plan (tile, L, S) = %s" % ((tile, L, S),))
     _full_case(w)
+
+
+def test_direct_to_lds_and_register_staged_block_scans_agree():
+    """bf16 at d = 128 has two block-scan kernels: the direct-to-LDS one (32-row blocks, the
+    default) and the register-staged one (64-row blocks, "staged_scan" switch).  Same arithmetic
+    up to block length and rounding points: they agree with each other far inside the tolerance,
+    each agrees with the oracle, and they are different code (outputs not bit-identical)."""
+    lam = [1.0, 0.9995, 0.97, 0.5]
+    w = synth.custom(2, 4, 1337, 128, lam, seed=4711, dtype="bf16")
+    xs = synth.draw(w)
+    q, k, v, g = _ref_inputs(xs, "bf16")
+    ref = (oracle.c_recurrence_fwd(q, k, v, lam),) + oracle.c_recurrence_bwd(q, k, v, lam, g)
+    for lseg in (None, 256):
+        direct = _run_gpu(w, xs, lseg=lseg)
+        binding.debug_set("staged_scan", 1)
+        try:
+            staged = _run_gpu(w, xs, lseg=lseg)
+        finally:
+            binding.debug_set("staged_scan", 0)
+        _compare(w, direct, ref, TOL["bf16"], "direct-to-LDS, lseg=%s" % lseg)
+        _compare(w, staged, ref, TOL["bf16"], "register-staged, lseg=%s" % lseg)
+        for a, b in zip(direct, staged):
+            assert oracle.rel_max_err(a, b) <= 1e-2
+            assert not np.array_equal(a, b)
