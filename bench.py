@@ -29,6 +29,14 @@ POINTS = [(32, 2048), (16, 4096), (8, 8192), (4, 16384), (2, 32768), (1, 65536)]
 MODEL_FLOPS_PER_TOKEN_HEAD = 30 * D * D
 
 
+def executed_flops_per_token_head(d, bk):
+    """Matrix-core flops the bf16 kernels issue per token and head, fwd + bwd: four scans, each
+    scores 2 bk d (the whole bk x bk tile of a 32-row block; three of four 32 x 32 tiles of a
+    64-row block), intra 2 bk d (same tiles), inter 2 d^2 and state update 2 d^2."""
+    tiles = 1.0 if bk == 32 else 0.75
+    return 4 * (2 * tiles * 2 * bk * d + 4 * d * d)
+
+
 def read_traffic_note():
     """HBM bytes per launch of the dominant kernel measured with rocprofv3
     --pmc (FETCH_SIZE, WRITE_SIZE), if a summary has been committed."""
@@ -44,25 +52,23 @@ def read_traffic_note():
 
 def cpu_baseline():
     """The CPU oracle (compiled token recurrence, fp64, OpenMP over scans), as
-    it stands, on a bounded sample of the same workload."""
-    import numpy as np
+    it stands, on a bounded sample of the same workload: the seeded (B=1, n=65536) sweep
+    point of `synth`, rounded to bf16 as the GPU sees it."""
+    import torch
     import oracle
     from paper_2405_17381_amd import synth
     w = synth.workload("c3_65536")
-    n = w.n
-    rng = np.random.default_rng(w.seed)
-    xs = [(rng.standard_normal((1, H, n, D), dtype=np.float32) / np.sqrt(D)).astype(np.float64)
-          for _ in range(4)]
+    xs = [x.to(torch.bfloat16).to(torch.float64).numpy() for x in synth.draw(w)]
     threads = oracle.oracle_threads()
     t0 = time.perf_counter()
     oracle.c_recurrence_fwd(xs[0], xs[1], xs[2], w.lambdas)
     oracle.c_recurrence_bwd(xs[0], xs[1], xs[2], w.lambdas, xs[3])
     dt = time.perf_counter() - t0
     return {
-        "value": n / dt, "unit": "tokens/s", "cores": min(threads, H), "kind": "oracle",
+        "value": w.n / dt, "unit": "tokens/s", "cores": min(threads, H), "kind": "oracle",
         "sample": "the whole (B=1, n=65536) sweep point (one batch of 65536 tokens), all 16 heads, "
-                  "d=128, fwd+bwd token recurrence in fp64; %.1f s wall on %d OpenMP threads "
-                  "(one thread per head)" % (dt, threads),
+                  "d=128, seeded inputs of the test-suite's workload c3_65536, fwd+bwd token recurrence "
+                  "in fp64; %.1f s wall on %d OpenMP threads (one thread per head)" % (dt, threads),
     }
 
 
@@ -162,16 +168,31 @@ def main():
         fb_med, fb_min = per_iteration_ms(lambda: (f(), b()))
         tps = TOKENS / (fb_med * 1e-3)
         tflops = tps * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12
-        _, L, S = binding.la_plan(B, H, n, D, binding.LA_BF16)
+        bk, L, S = binding.la_plan(B, H, n, D, binding.LA_BF16)
+        ex_tflops = tps * H * executed_flops_per_token_head(D, bk) / 1e12
         sweep.append({"B": B, "n": n, "fwd_ms": round(f_med, 4), "fwd_ms_min": round(f_min, 4),
                       "bwd_ms": round(b_med, 4), "bwd_ms_min": round(b_min, 4),
                       "fwd_bwd_ms": round(fb_med, 4), "fwd_bwd_ms_min": round(fb_min, 4),
                       "tokens_per_s": round(tps, 1), "model_tflops": round(tflops, 2),
                       "pct_mfma_bf16_peak": round(100.0 * tflops / MFMA_BF16_PEAK_TFLOPS, 2),
-                      "segment_len": L, "segments": S})
+                      "executed_tflops": round(ex_tflops, 2),
+                      "pct_mfma_bf16_peak_executed": round(100.0 * ex_tflops / MFMA_BF16_PEAK_TFLOPS, 2),
+                      "algorithmic_TBps": round(28 * D * H * tps / 1e12, 3),
+                      "block_len": bk, "segment_len": L, "segments": S})
     rates = [p["tokens_per_s"] for p in sweep]
     near_constant = {"min_over_max_tokens_per_s": round(min(rates) / max(rates), 3),
-                     "note": "per-point rates from the median back-to-back fwd+bwd time of 20 iterations"}
+                     "target": "north_star: near-constant from 2K to 64K; proposed bound >= 0.8 (0.9 asked later)",
+                     "note": "per-point rates from the median back-to-back fwd+bwd time of 20 iterations; the "
+                             "four points with fewer than 256 (batch, head) scans pay the segment-state "
+                             "pre-pass (extra reads of K, V / dO, Q), the first two do not"}
+    if len(sweep) >= 2:
+        # time per sequence against sequence length: least-squares slope in log-log (1 = linear in n)
+        import math
+        xs_ = [math.log(p["n"]) for p in sweep]
+        ys_ = [math.log(p["fwd_bwd_ms"] / p["B"]) for p in sweep]
+        mx, my = sum(xs_) / len(xs_), sum(ys_) / len(ys_)
+        near_constant["loglog_slope_time_per_sequence_vs_n"] = round(
+            sum((x - mx) * (y - my) for x, y in zip(xs_, ys_)) / sum((x - mx) ** 2 for x in xs_), 4)
 
     # ---- roofline of the dominant kernel: the block-scan kernel -------------------
     # One launch streams three [tokens, H, d] bf16 operands in and one out:
@@ -191,7 +212,7 @@ def main():
     alg_bytes = alg_bytes_per_point * len(POINTS) * args.steps
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
     per_launch = alg_bytes / max(launches, 1)
-    roofline = {"bound": "hbm", "kernel": "la_scan_bf16<128> (block scan: fwd, dQ, paired dK/dV launches)",
+    roofline = {"bound": "hbm", "kernel": "la_scan_bf16_dma (block scan, d=128: fwd, dQ, paired dK/dV launches)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic_note(),
                 "launches": launches, "avg_launch_ms": round(scan_ms / max(launches, 1), 5),
@@ -239,21 +260,22 @@ def main():
 
     # ---- gated SRMSNorm output stage (next row): same tensors as the (1, 65536) point ---------
     tg = views(1, TOKENS)
-    def _time(fn, it=10):
-        fn()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(it):
-            fn()
-        e1.record()
-        e1.synchronize()
-        return e0.elapsed_time(e1) / it
-    gf = _time(lambda: binding.la_gate_norm_fwd(tg["O"], tg["V"], 0.0, Y=tg["dQ"]))
-    gb = _time(lambda: binding.la_gate_norm_bwd(tg["O"], tg["V"], tg["dO"], 0.0, dO=tg["dK"], dU=tg["dV"]))
+    leg_min = {}
+
+    def _time(fn, it=20, key=None):
+        """Median of `it` single-call timings after 5 warm-up calls (the sweep's protocol); the
+        minimum is kept in `leg_min` under `key`."""
+        med, mn = per_iteration_ms(fn, warm=5, iters=it)
+        if key:
+            leg_min[key] = round(mn, 4)
+        return med
+    gf = _time(lambda: binding.la_gate_norm_fwd(tg["O"], tg["V"], 0.0, Y=tg["dQ"]), key="gate_norm_fwd")
+    gb = _time(lambda: binding.la_gate_norm_bwd(tg["O"], tg["V"], tg["dO"], 0.0, dO=tg["dK"], dU=tg["dV"]),
+               key="gate_norm_bwd")
     tensor_bytes = 2 * numel
     gate_norm = {"workload": "Y = SRMSNorm(O) * U and its backward, [1,16,65536,128] bf16",
                  "fwd_ms": round(gf, 4), "bwd_ms": round(gb, 4),
+                 "fwd_ms_min": leg_min["gate_norm_fwd"], "bwd_ms_min": leg_min["gate_norm_bwd"],
                  "fwd_GBps": round(3 * tensor_bytes / (gf * 1e-3) / 1e9, 1),
                  "bwd_GBps": round(5 * tensor_bytes / (gb * 1e-3) / 1e9, 1),
                  "note": "algorithmic bytes: 3 tensors forward, 5 backward; HBM-bound"}
@@ -262,10 +284,11 @@ def main():
     swish = []
     for sB, sn in ((32, 2048), (1, TOKENS)):
         t = views(sB, sn)
-        sf = _time(lambda: binding.la_fwd_swish(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=ws))
+        sf = _time(lambda: binding.la_fwd_swish(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=ws), key="sf")
         sb = _time(lambda: binding.la_bwd_swish(t["Q"], t["K"], t["V"], lam, t["dO"], dQp=t["dQ"], dKp=t["dK"],
-                                                dV=t["dV"], workspace=ws))
+                                                dV=t["dV"], workspace=ws), key="sb")
         swish.append({"B": sB, "n": sn, "fwd_ms": round(sf, 4), "bwd_ms": round(sb, 4),
+                      "fwd_ms_min": leg_min["sf"], "bwd_ms_min": leg_min["sb"],
                       "tokens_per_s": round(TOKENS / ((sf + sb) * 1e-3), 1),
                       "algorithmic_GBps": round(16 * tensor_bytes / ((sf + sb) * 1e-3) / 1e9, 1)})
     swish_fused = {"workload": "la_fwd_swish + la_bwd_swish, H=16, d=128, bf16, 65536 tokens",
@@ -310,11 +333,70 @@ def main():
         binding.la_fwd(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=fws)
         binding.la_bwd_saved(t["Q"], t["K"], t["V"], lam, t["dO"], fws, dQ=t["dQ"], dK=t["dK"], dV=t["dV"],
                              workspace=ws)
-    sv = _time(train_step, it=20)
-    saved_states = {"workload": "la_fwd + la_bwd_saved (backward reuses the forward pass's segment states), "
-                                "[1,16,65536,128] bf16",
-                    "fwd_bwd_ms": round(sv, 4), "tokens_per_s": round(TOKENS / (sv * 1e-3), 1),
-                    "plain_fwd_bwd_ms": sweep[-1]["fwd_bwd_ms"] if sweep[-1]["n"] == TOKENS else None}
+    sv = _time(train_step, it=20, key="saved")
+    saved_states = {"workload": "la_fwd + la_bwd_saved (backward reuses the forward pass's segment states: the "
+                                "training-step form), [1,16,65536,128] bf16",
+                    "fwd_bwd_ms": round(sv, 4), "fwd_bwd_ms_min": leg_min["saved"],
+                    "tokens_per_s": round(TOKENS / (sv * 1e-3), 1),
+                    "plain_fwd_bwd_ms": sweep[-1]["fwd_bwd_ms"] if sweep[-1]["n"] == TOKENS else None,
+                    "note": "not the headline: la_bwd takes no saved context by contract"}
+
+    # ---- the other bf16 configurations (parity cases; timed here so that their rates come from the
+    # same run and protocol): C2 (TNL-400M-shaped layer, d = 64), C4 (TNL-7B-shaped layer), C5 (one
+    # 131072-token sequence, half of the heads without decay) ------------------------------------------
+    other_configs = []
+    for name in ("c2", "c4", "c5"):
+        w = synth.workload(name)
+        el = w.B * w.H * w.n * w.d
+        gsc = 1.0 / (w.d ** 0.5)
+        xs = [(torch.randn(el, generator=gen, device=dev, dtype=torch.float32) * gsc).to(torch.bfloat16)
+              .view(w.B, w.H, w.n, w.d) for _ in range(3)]
+        if name == "c4":                                     # Q, K = silu(N(0,1)) / sqrt(d)
+            for i in range(2):
+                xs[i] = (torch.nn.functional.silu(xs[i].float() / gsc) * gsc).to(torch.bfloat16)
+        xs.append(torch.randn(el, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+                  .view(w.B, w.H, w.n, w.d))
+        outs = [torch.empty_like(xs[0]) for _ in range(4)]
+        need = binding.la_workspace_bytes(w.B, w.H, w.n, w.d, binding.LA_BF16, True)
+        cws = ws if need <= ws.numel() else torch.empty(need, dtype=torch.uint8, device=dev)
+        cf_ = lambda: binding.la_fwd(xs[0], xs[1], xs[2], w.lambdas, O=outs[0], workspace=cws)
+        cb_ = lambda: binding.la_bwd(xs[0], xs[1], xs[2], w.lambdas, xs[3], dQ=outs[1], dK=outs[2], dV=outs[3],
+                                     workspace=cws)
+        f_med, f_min = per_iteration_ms(cf_)
+        b_med, b_min = per_iteration_ms(cb_)
+        fb_med, fb_min = per_iteration_ms(lambda: (cf_(), cb_()))
+        tok = w.B * w.n
+        tps = tok / (fb_med * 1e-3)
+        bk, L, S = binding.la_plan(w.B, w.H, w.n, w.d, binding.LA_BF16)
+        mt = tps * w.H * 30 * w.d * w.d / 1e12
+        et = tps * w.H * executed_flops_per_token_head(w.d, bk) / 1e12
+        other_configs.append({
+            "config": name, "B": w.B, "H": w.H, "n": w.n, "d": w.d,
+            "fwd_ms": round(f_med, 4), "fwd_ms_min": round(f_min, 4), "bwd_ms": round(b_med, 4),
+            "bwd_ms_min": round(b_min, 4), "fwd_bwd_ms": round(fb_med, 4), "fwd_bwd_ms_min": round(fb_min, 4),
+            "tokens_per_s": round(tps, 1), "algorithmic_TBps": round(28 * w.d * w.H * tps / 1e12, 3),
+            "model_tflops": round(mt, 2), "pct_mfma_bf16_peak": round(100.0 * mt / MFMA_BF16_PEAK_TFLOPS, 2),
+            "executed_tflops": round(et, 2),
+            "pct_mfma_bf16_peak_executed": round(100.0 * et / MFMA_BF16_PEAK_TFLOPS, 2),
+            "block_len": bk, "segment_len": L, "segments": S})
+        del xs, outs, cws
+    torch.cuda.empty_cache()
+
+    # ---- what the matrix cores deliver with nothing in the way: the measured bf16 denominator -----
+    sink = torch.zeros(1, device=dev, dtype=torch.float32)
+    mf_iters, mf_wgs = 4000, 8 * 256
+    mf_flops = binding.debug_mfma_rate(mf_wgs, mf_iters, sink)
+    mf_med, mf_min = per_iteration_ms(lambda: binding.debug_mfma_rate(mf_wgs, mf_iters, sink), warm=3, iters=10)
+    mf_tflops = mf_flops / (mf_med * 1e-3) / 1e12
+    mfma_measured = {
+        "kernel": "register-only loop of v_mfma_f32_32x32x16_bf16, 4 independent accumulator tiles per wave, "
+                  "%d workgroups x 4 waves x %d iterations" % (mf_wgs, mf_iters),
+        "ms": round(mf_med, 4), "ms_min": round(mf_min, 4), "measured_tflops": round(mf_tflops, 1),
+        "published_tflops": MFMA_BF16_PEAK_TFLOPS,
+        "implied_clock_GHz": round(mf_tflops * 1e12 / (256 * 4 * 1024.0) / 1e9, 3),
+        "note": "implied clock = measured rate / (256 CUs x 4 SIMDs x 1024 flops per cycle), i.e. the clock at "
+                "which the published 2.5 PFLOP/s (at 2.4 GHz) scales to the measured rate",
+        "sweep_pct_of_measured_model_flops": None, "sweep_pct_of_measured_executed_flops": None}
 
     # ---- fp32 path (matrix-core fp32 kernel at d = 128): the (32, 2048) point in fp32 ---------------
     fB, fn = 32, 2048
@@ -332,6 +414,21 @@ def main():
     del ft, fo
 
     total_tflops = value * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12
+    total_ex_tflops = value * H * executed_flops_per_token_head(D, sweep[0]["block_len"]) / 1e12
+    mfma_measured["sweep_pct_of_measured_model_flops"] = round(100.0 * total_tflops / mf_tflops, 2)
+    mfma_measured["sweep_pct_of_measured_executed_flops"] = round(100.0 * total_ex_tflops / mf_tflops, 2)
+    # The target of the benchmark spec (>= 40 % of the bf16 MFMA peak at d = 128, 30 d^2 model flops) needs
+    # 28 d bytes per token per head to move at this rate:
+    target_tps = 0.40 * MFMA_BF16_PEAK_TFLOPS * 1e12 / (H * MODEL_FLOPS_PER_TOKEN_HEAD)
+    target = {"north_star": ">= 40 % of bf16 MFMA peak at d = 128, near-constant tokens/s from 2K to 64K",
+              "met": bool(100.0 * total_tflops / MFMA_BF16_PEAK_TFLOPS >= 40.0),
+              "tokens_per_s_needed": round(target_tps, 1),
+              "HBM_TBps_needed_at_28d_bytes": round(28 * D * H * target_tps / 1e12, 2),
+              "measured_stream_TBps": round(stream_gbs / 1e3, 2),
+              "note": "the path moves 28 d bytes per token per head (14 tensor passes) and is HBM-bound; at the "
+                      "rate a plain 3-in / 1-out streaming kernel reaches on this box the ceiling is "
+                      "%.1f %% of the MFMA peak" % (100.0 * (stream_gbs * 1e9 / (28 * D * H)) * H *
+                                                    MODEL_FLOPS_PER_TOKEN_HEAD / 1e12 / MFMA_BF16_PEAK_TFLOPS)}
     out = {
         "metric": "fwd+bwd tokens/s (causal linear attention with decay, bf16, d=128, seq-len sweep "
                   "2K-64K at 64K tokens per batch)",
@@ -345,6 +442,11 @@ def main():
                    "tokens_per_step": tokens_per_step, "H": H, "d": D},
         "model_tflops": round(total_tflops, 2),
         "pct_mfma_bf16_peak": round(100.0 * total_tflops / MFMA_BF16_PEAK_TFLOPS, 2),
+        "executed_tflops": round(total_ex_tflops, 2),
+        "pct_mfma_bf16_peak_executed": round(100.0 * total_ex_tflops / MFMA_BF16_PEAK_TFLOPS, 2),
+        "target": target,
+        "mfma_measured": mfma_measured,
+        "other_configs": other_configs,
         "sweep": sweep,
         "near_constant": near_constant,
         "roofline": roofline,

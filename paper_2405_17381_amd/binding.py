@@ -21,7 +21,7 @@ EXPORTS = ("la_workspace_bytes", "la_fwd", "la_bwd", "la_fwd_state", "la_decode_
            "la_lrpe_rotate_fwd", "la_lrpe_rotate_bwd", "la_fwd_strided", "la_bwd_strided", "la_bwd_saved", "la_strerror", "la_plan",
            "la_profile_enable", "la_profile_collect", "la_fwd_static")
 # exported for tests and tuning, declared in csrc/la_debug.h, not in include/la.h
-DEBUG_EXPORTS = ("la_debug_set", "la_debug_get")
+DEBUG_EXPORTS = ("la_debug_set", "la_debug_get", "la_debug_mfma_rate")
 _lib = None
 
 
@@ -59,6 +59,8 @@ def load_library():
     lib.la_debug_set.restype = ci
     lib.la_debug_get.argtypes = [ctypes.c_char_p]
     lib.la_debug_get.restype = ctypes.c_long
+    lib.la_debug_mfma_rate.argtypes = [ci, ci, vp, vp]
+    lib.la_debug_mfma_rate.restype = ci
     lib.la_fwd_swish.argtypes = lib.la_fwd.argtypes
     lib.la_fwd_swish.restype = ci
     lib.la_bwd_swish.argtypes = lib.la_bwd.argtypes
@@ -201,6 +203,17 @@ def debug_set(name: str, value: int) -> None:
 
 def debug_get(name: str) -> int:
     return int(load_library().la_debug_get(name.encode()))
+
+
+def debug_mfma_rate(workgroups: int, iters: int, sink: torch.Tensor) -> int:
+    """Launch the register-only MFMA loop (csrc/la_debug.h) on the current stream; returns the
+    number of floating-point operations the launch executes."""
+    with torch.cuda.device(sink.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        rc = load_library().la_debug_mfma_rate(int(workgroups), int(iters), sink.data_ptr(), stream)
+    if rc != 0:
+        raise LaError(rc, "la_debug_mfma_rate")
+    return workgroups * 4 * 4 * iters * 2 * 32 * 32 * 16
 
 
 @contextlib.contextmanager

@@ -54,6 +54,7 @@ struct Switches {
     std::atomic<long> no_decay_skip{0};  // != 0: the segment-state pre-pass reads every block
     std::atomic<long> f32_plain{0};      // != 0: fp32 at d = 128 runs the FMA kernel
     std::atomic<long> store_policy{0};   // direct-to-LDS scan: 2 = ordinary instead of non-temporal result stores
+    std::atomic<long> staged_prepass{0}; // != 0: bf16 at d = 128 runs the register-staged segment-state pre-pass
     std::atomic<long> ablate{0};         // 1..3: measurement-only variants of the direct-to-LDS scan
     std::atomic<long> staged_scan{0};    // != 0: bf16 at d = 128 runs the register-staged block scan
                                          // (64-row blocks) instead of the direct-to-LDS one (32-row)
@@ -68,6 +69,7 @@ std::atomic<long> *find_switch(const char *name)
     if (!std::strcmp(name, "f32_plain")) return &g_sw.f32_plain;
     if (!std::strcmp(name, "staged_scan")) return &g_sw.staged_scan;
     if (!std::strcmp(name, "ablate")) return &g_sw.ablate;
+    if (!std::strcmp(name, "staged_prepass")) return &g_sw.staged_prepass;
     if (!std::strcmp(name, "store_policy")) return &g_sw.store_policy;
     return nullptr;
 }
@@ -248,6 +250,19 @@ hipError_t launch_bf16_dma(const ScanLaunch &a, const LaLambdas &lams, hipStream
               : launch_bf16_dma_variant<REV, false, 0>(a, lams, s);
 }
 
+hipError_t launch_prepass_bf16_dma(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
+{
+    using Cfg = DmaPrepassCfg;
+    auto kern = la_prepass_bf16_dma;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
+    if (attr_err != hipSuccess) return attr_err;
+    dim3 grid((unsigned)(a.items * a.nroles)), block(Cfg::NT);
+    hipLaunchKernelGGL(kern, grid, block, Cfg::lds_bytes, s, a, lams);
+    return hipGetLastError();
+}
+
 template <int D, bool ACT>
 hipError_t launch_prepass_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
@@ -299,7 +314,10 @@ hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
         const bool act = (a.r[0].act | a.r[a.nroles - 1].act) != 0;
         if (STATE_ONLY) {
             if (act) return d == 64 ? launch_prepass_bf16<64, true>(a, lams, s) : launch_prepass_bf16<128, true>(a, lams, s);
-            return d == 64 ? launch_prepass_bf16<64, false>(a, lams, s) : launch_prepass_bf16<128, false>(a, lams, s);
+            if (d == 64) return launch_prepass_bf16<64, false>(a, lams, s);
+            if (g_sw.staged_scan.load(std::memory_order_relaxed) || g_sw.staged_prepass.load(std::memory_order_relaxed))
+                return launch_prepass_bf16<128, false>(a, lams, s);
+            return launch_prepass_bf16_dma(a, lams, s);
         }
         if (act) return d == 64 ? launch_bf16<64, REV, true>(a, lams, s) : launch_bf16<128, REV, true>(a, lams, s);
         if (d == 64) return launch_bf16<64, REV, false>(a, lams, s);
@@ -926,6 +944,13 @@ int la_debug_set(const char *name, long value)
     if (!sw) return LA_ERR_NULL;
     sw->store(value, std::memory_order_relaxed);
     return LA_OK;
+}
+
+int la_debug_mfma_rate(int workgroups, int iters, float *sink, void *hip_stream)
+{
+    if (workgroups < 1 || iters < 1 || !sink) return LA_ERR_SHAPE;
+    hipLaunchKernelGGL(la_mfma_rate_kernel, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, sink, iters);
+    return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
 
 long la_debug_get(const char *name)

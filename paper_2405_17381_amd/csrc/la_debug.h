@@ -18,6 +18,8 @@
  *   "ablate"         1..3: measurement-only variants of the direct-to-LDS block scan that
  *                    leave work out (1: no result stores, 2: loads and barriers only,
  *                    3: arithmetic only); their results are wrong by design
+ *   "staged_prepass" != 0: bf16 at d = 128 runs the register-staged segment-state pre-pass
+ *                    instead of the direct-to-LDS one
  *   "store_policy"   2: the direct-to-LDS block scan stores its results with ordinary instead
  *                    of non-temporal stores
  *   "staged_scan"    != 0: bf16 at d = 128 runs the register-staged block scan (64-row
@@ -33,6 +35,13 @@ extern "C" {
 #endif
 int la_debug_set(const char *name, long value);
 long la_debug_get(const char *name);
+/*
+ * Measurement aid for the benchmark's matrix-core denominator: launches `workgroups`
+ * workgroups of four waves that each issue 4 * iters v_mfma_f32_32x32x16_bf16 from registers
+ * only (2 * 32 * 32 * 16 flops each).  `sink` is a DEVICE pointer to one float that is never
+ * written in practice.  The caller times the launch.  Returns an la_status.
+ */
+int la_debug_mfma_rate(int workgroups, int iters, float *sink, void *hip_stream);
 #ifdef __cplusplus
 }
 #endif

@@ -427,3 +427,163 @@ __global__ __launch_bounds__(256, 2) void la_scan_bf16_dma(ScanLaunch launch, La
             }
     }
 }
+
+// ---- segment-state pre-pass on the same machinery --------------------------------------
+// The local end state of every segment (see la_kernels_prepass.h for what it is and how the
+// launch is laid out: roles, head order, decay cut-off), computed as the state update of the
+// block scan alone: per 32-row block the Bm and C tiles arrive by direct loads (2 x 8 KB per
+// stage, five stages: four blocks of prefetch, so that the short per-block chain of a slowly
+// decaying head never waits for memory), Bm^T and this wave's C fragments come from the
+// transposing reads, and the decay is folded into the weights put on the C fragments (row r
+// of block k is weighted by its full distance to the segment's far end), so the accumulator
+// is never rescaled.  One barrier per block, no stores until the state is written out.
+struct DmaPrepassCfg {
+    static constexpr int D = 128, BK = 32, NS = 5, NT = 256;
+    static constexpr int TILE_BYTES = BK * D * 2;
+    static constexpr int STAGE_BYTES = 2 * TILE_BYTES;       // Bm, C
+    static constexpr size_t lds_bytes = (size_t)NS * STAGE_BYTES;   // 81920
+};
+
+__global__ __launch_bounds__(256, 2) void la_prepass_bf16_dma(ScanLaunch launch, LaLambdas lams)
+{
+    using Cfg = DmaPrepassCfg;
+    constexpr int D = Cfg::D, BK = Cfg::BK, NS = Cfg::NS, PF = NS - 1;
+    constexpr int KS_B = BK / 16, MT_D = D / 32;
+    constexpr int LOADS = 4;                   // direct loads per wave and block (2 tiles x 2 slots)
+
+    extern __shared__ __align__(16) unsigned char smem_dma[];
+
+    const int tid = threadIdx.x;
+    const int l = tid & 63, l32 = l & 31, g = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const int role = launch.nroles == 2 ? (int)(blockIdx.x / launch.items) : 0;
+    const int item = launch.nroles == 2 ? (int)(blockIdx.x % launch.items) : (int)blockIdx.x;
+    const ScanArgs &a = launch.r[role];
+    const int seg = item % a.S;
+    const int bh = item / a.S;                               // (head in dispatch order, batch)
+    const int scan = (bh % a.B) * a.H + lams.order[bh / a.B];
+    const bool rev = a.rev != 0;
+    if (!rev && seg == a.S - 1) return;                      // never consumed
+    if (rev && seg == 0) return;
+
+    const float lg = lams.lg2[scan % a.H];
+    auto pw = [lg](int k) -> float { return exp2f((float)k * lg); };
+
+    const int seg_lo = seg * a.L;
+    const int seg_hi = min(a.n, seg_lo + a.L);
+    const int nblk = (seg_hi - seg_lo + BK - 1) / BK;
+    int ib0 = 0;                                             // decay cut-off
+    if (a.skip_bits > 0.f && lg < 0.f) {
+        const float reach = a.skip_bits / -lg;
+        if (reach < (float)(nblk * BK)) ib0 = max(0, nblk - ((int)(reach / BK) + 2));
+    }
+
+    const size_t base = (size_t)scan * a.n * D;
+    const uint16_t *gB = (const uint16_t *)a.Bm + base;
+    const uint16_t *gC = (const uint16_t *)a.C + base;
+    float *gSt = a.states + ((size_t)scan * a.S + seg) * (size_t)(D * D);
+
+    float wt[16];                              // weight of the token in slot (ks, e) inside a block
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int key = 8 * (v >> 2) + 4 * g + (v & 3);
+        wt[v] = rev ? pw(key) : pw(BK - 1 - key);
+    }
+    const int a4 = l & 3, b4 = (l >> 2) & 3, h16 = (l >> 4) & 1;
+    const int tr_base = (4 * g + b4) * 256 + 8 * (a4 & 1);
+    const int tr_sw = (2 * h16 + (a4 >> 1)) ^ (8 * g + 2 * b4);
+    int dma_row[2], dma_col[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        dma_row[j] = 4 * (2 * w + j) + (l >> 4);
+        dma_col[j] = 8 * ((l & 15) ^ dma_sw(dma_row[j]));
+    }
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(la_lds_void *)smem_dma);
+
+    f32x16_t st[MT_D];
+#pragma unroll
+    for (int mt = 0; mt < MT_D; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) st[mt][v] = 0.0f;
+
+    const auto blk_of = [&](int ib) { return rev ? (nblk - 1 - ib) : ib; };
+    auto issue = [&](int ib, int stage) {
+        const int t0 = seg_lo + blk_of(ib) * BK;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const size_t off = (size_t)min(t0 + dma_row[j], seg_hi - 1) * D + dma_col[j];
+            const uint32_t dst = lds0 + stage * Cfg::STAGE_BYTES + (2 * w + j) * 1024;
+            dma_load16<true>(gB + off, dst);
+            dma_load16<true>(gC + off, dst + Cfg::TILE_BYTES);
+        }
+    };
+
+#pragma unroll
+    for (int i = 0; i < PF; ++i)
+        if (ib0 + i < nblk) issue(ib0 + i, i);
+
+    int stage = 0;
+    for (int ib = ib0; ib < nblk; ++ib) {
+        const int blk = blk_of(ib);
+        const int t0 = seg_lo + blk * BK;
+        unsigned char *sb = smem_dma + stage * Cfg::STAGE_BYTES;
+        // younger than this block's loads: those of the next min(PF - 1, blocks left) blocks
+        const int ahead = min(PF - 1, nblk - 1 - ib);
+        if (ahead >= 3) la_wait_vm<3 * LOADS>();
+        else if (ahead == 2) la_wait_vm<2 * LOADS>();
+        else if (ahead == 1) la_wait_vm<LOADS>();
+        else la_wait_vm<0>();
+        if (t0 + BK > seg_hi) {                 // partial block: zero padding (exact)
+            const U4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                if (t0 + dma_row[j] >= seg_hi) {
+                    unsigned char *dst = sb + (2 * w + j) * 1024 + 16 * l;
+                    *(U4 *)dst = z;
+                    *(U4 *)(dst + Cfg::TILE_BYTES) = z;
+                }
+        }
+        LA_LDS_BARRIER();                       // landed for every wave; the previous block's stage is free
+        if (ib + PF < nblk) issue(ib + PF, stage >= 1 ? stage - 1 : NS - 1);
+
+        const unsigned char *sB = sb, *sC = sb + Cfg::TILE_BYTES;
+        // distance of this block to the segment's far end, folded into the weights
+        const float mu = rev ? pw(blk * BK) : pw((nblk - 1 - blk) * BK);
+        U4 cw[KS_B];
+#pragma unroll
+        for (int ks = 0; ks < KS_B; ++ks) {
+            const unsigned char *p = sC + tr_base + 16 * ks * 256;
+            const U2 lo = lds_read_tr(p + ((((4 * w) ^ tr_sw)) << 4));
+            const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * w) ^ tr_sw ^ 1)) << 4));
+            const U4 cf = {lo[0], lo[1], hi[0], hi[1]};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                cw[ks][e] = pack2_bf16(bf16_lo(cf[e]) * (wt[8 * ks + 2 * e] * mu),
+                                       bf16_hi(cf[e]) * (wt[8 * ks + 2 * e + 1] * mu));
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT_D; ++mt) {
+            U4 bt[KS_B];
+#pragma unroll
+            for (int ks = 0; ks < KS_B; ++ks) {
+                const unsigned char *p = sB + tr_base + 16 * ks * 256;
+                const U2 lo = lds_read_tr(p + ((((4 * mt) ^ tr_sw)) << 4));
+                const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * mt) ^ tr_sw ^ 1)) << 4));
+                bt[ks] = U4{lo[0], lo[1], hi[0], hi[1]};
+            }
+            LA_BATCH_FENCE();
+#pragma unroll
+            for (int ks = 0; ks < KS_B; ++ks) st[mt] = mfma32(bt[ks], cw[ks], st[mt]);
+        }
+        stage = stage + 1 < NS ? stage + 1 : 0;
+    }
+
+#pragma unroll
+    for (int mt = 0; mt < MT_D; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int i = 32 * mt + 8 * (v >> 2) + 4 * g + (v & 3);
+            gSt[(size_t)i * D + 32 * w + l32] = st[mt][v];
+        }
+}

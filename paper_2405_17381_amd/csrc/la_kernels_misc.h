@@ -118,3 +118,34 @@ __global__ __launch_bounds__(256) void la_decode_kernel(const void *q_, const vo
         }
     }
 }
+
+// Measurement aid (reached only through la_debug_mfma_rate): what the matrix cores deliver
+// on v_mfma_f32_32x32x16_bf16 when nothing else is in the way.  Every wave keeps four
+// independent accumulator tiles busy from registers only; the result is stored only if it
+// equals a value it cannot take, so that the loop survives and no memory traffic happens.
+typedef __bf16 misc_bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float misc_f32x16_t __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void la_mfma_rate_kernel(float *sink, int iters)
+{
+    misc_f32x16_t acc[4];
+    misc_bf16x8_t a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (__bf16)(float)((threadIdx.x + e) & 3);
+        b[e] = (__bf16)(float)((threadIdx.x * 3 + e) & 1);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+    }
+    float sum = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum += acc[j][v];
+    if (sum == -1.0f) sink[0] = sum;          // never true: the sums are non-negative
+}
