@@ -72,6 +72,53 @@ def cpu_baseline():
     }
 
 
+def ablation(binding, torch, views, lam, ws):
+    """Where the block scan's time goes: the same launches with work left out.  Every variant is
+    selected by a debug switch of the library (csrc/la_debug.h); variants 1-4 of "ablate" give wrong
+    results by design.  Medians of 20 single calls after 5 warm-up calls; every case is measured
+    twice, interleaved, to show the run-to-run spread."""
+    def med(fn):
+        for _ in range(5):
+            fn()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+        torch.cuda.synchronize()
+        for e0, e1 in evs:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+        return round(0.5 * (ms[9] + ms[10]), 4)
+
+    cases = [("default (direct-to-LDS scan, 32-row blocks, non-temporal result stores)", {}),
+             ("register-staged scan and pre-pass (64-row blocks)", {"staged_scan": 1}),
+             ("register-staged pre-pass only", {"staged_prepass": 1}),
+             ("ordinary result stores", {"store_policy": 2}),
+             ("ablate 1: no result stores", {"ablate": 1}),
+             ("ablate 2: loads, waits and barriers only", {"ablate": 2}),
+             ("ablate 3: arithmetic only (no loads, no stores)", {"ablate": 3}),
+             ("ablate 4: loads, barriers and result stores, no arithmetic", {"ablate": 4})]
+    out = {"protocol": "median ms of 20 calls, two interleaved rounds; fwd = la_fwd, bwd = la_bwd, "
+                       "fwd_bwd = the two back to back; H=16, d=128, bf16, 65536 tokens", "cases": []}
+    fns = {}
+    for B, n in ((32, 2048), (1, 65536)):
+        t = views(B, n)
+        f = lambda t=t: binding.la_fwd(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=ws)
+        b = lambda t=t: binding.la_bwd(t["Q"], t["K"], t["V"], lam, t["dO"], dQ=t["dQ"], dK=t["dK"],
+                                       dV=t["dV"], workspace=ws)
+        fns[(B, n)] = (f, b)
+    med(fns[(32, 2048)][0])                                   # clocks up before the first case
+    for rnd in range(2):
+        for label, sw in cases:
+            with binding.debug(**sw):
+                row = {"case": label, "round": rnd}
+                for (B, n), (f, b) in fns.items():
+                    row["B%d_n%d" % (B, n)] = {"fwd_ms": med(f), "bwd_ms": med(b),
+                                               "fwd_bwd_ms": med(lambda: (f(), b()))}
+            out["cases"].append(row)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -80,6 +127,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--point", type=int, default=0,
                     help="profiling aid: restrict the step to the sweep point with this n")
+    ap.add_argument("--ablation", action="store_true",
+                    help="measurement aid: instead of the benchmark, time the (32, 2048) and (1, 65536) points "
+                         "with parts of the block scan left out or replaced (library debug switches) and "
+                         "print one JSON line")
     ap.add_argument("--calib-copy", action="store_true",
                     help="profiling aid: also run a plain 256 MiB -> 256 MiB device copy per step, "
                          "whose FETCH_SIZE / WRITE_SIZE readings calibrate the HBM counters")
@@ -129,6 +180,10 @@ def main():
         if args.calib_copy:
             # an elementwise kernel that reads 256 MiB and writes 256 MiB
             torch.add(flat["Q"], 0, out=flat["O"])
+
+    if args.ablation:
+        print(json.dumps(ablation(binding, torch, views, lam, ws)), flush=True)
+        return
 
     for _ in range(args.warmup):
         step()

@@ -55,9 +55,11 @@ extern "C" {
 #endif
 
 #define LA_MAX_HEADS 256
-#define LA_MAX_SEQ_LEN 2147483519   /* 2^31 - 1 - 128: longer n gives LA_ERR_SHAPE */
+#define LA_MAX_SEQ_LEN 1073741823   /* 2^30 - 1: longer n gives LA_ERR_SHAPE */
 
-typedef enum { LA_F32 = 0, LA_BF16 = 1 } la_dtype;
+/* (the two bounds only widen the enum's range to that of int, so that any value a caller
+ * passes can be inspected and refused with LA_ERR_DTYPE) */
+typedef enum { LA_F32 = 0, LA_BF16 = 1, LA_DTYPE_MIN_ = -2147483647 - 1, LA_DTYPE_MAX_ = 2147483647 } la_dtype;
 
 typedef enum {
     LA_OK = 0,

@@ -125,7 +125,7 @@ Plan make_plan(int B, int H, int n, int d, la_dtype dt)
         L = (int)(v < round_up(n, gran) ? v : round_up(n, gran));
     }
     p.L = L;
-    p.S = (n + L - 1) / L;
+    p.S = (int)(((long)n + L - 1) / L);
     return p;
 }
 
@@ -133,7 +133,7 @@ int check_common(int B, int H, int n, int d, la_dtype dt)
 {
     if (dt != LA_F32 && dt != LA_BF16) return LA_ERR_DTYPE;
     if (B < 1 || H < 1 || n < 1 || H > LA_MAX_HEADS) return LA_ERR_SHAPE;
-    if (n > LA_MAX_SEQ_LEN) return LA_ERR_SHAPE;        // keeps round_up(n, tile) and seg_lo + L in int
+    if (n > LA_MAX_SEQ_LEN) return LA_ERR_SHAPE;        // keeps round_up(n, tile) and seg_lo + L (< 2 n) in int
     if (d != 64 && d != 128) return LA_ERR_SHAPE;
     if ((long)B * H > (long)INT32_MAX / 4096) return LA_ERR_SHAPE;
     return LA_OK;
@@ -214,11 +214,11 @@ hipError_t launch_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s
     return hipGetLastError();
 }
 
-template <bool REV, bool NT_STORE, int ABL>
+template <bool REV, bool NT_STORE, int ABL, int NS = 3>
 hipError_t launch_bf16_dma_variant(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
-    using Cfg = DmaCfg;
-    auto kern = la_scan_bf16_dma<REV, NT_STORE, ABL>;
+    using Cfg = DmaCfg<NS>;
+    auto kern = la_scan_bf16_dma<REV, NT_STORE, ABL, NS>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });

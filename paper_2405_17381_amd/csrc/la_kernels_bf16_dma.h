@@ -57,30 +57,42 @@ typedef __attribute__((address_space(3))) void la_lds_void;
 typedef short la_s4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) la_s4 la_lds_s4;
 
+// NS stages = NS - 1 blocks of prefetch.  NS = 3 lets two workgroups share a compute unit
+// (80 KB each).  Measured: NS = 2 is as fast when 512 workgroups are resident and 4 % slower
+// with 256; NS = 4 and 6 (one workgroup per compute unit) are 15 to 30 % slower: the path is
+// not short of bytes in flight.
+template <int NS_>
 struct DmaCfg {
     static constexpr int D = 128, BK = 32;
-    static constexpr int NS = 3;                             // stages: NS - 1 blocks of prefetch
+    static constexpr int NS = NS_;
     static constexpr int NW = 4, NT = 64 * NW;
     static constexpr int NTILE = 3;                          // tiles per stage: A, Bm, C
     static constexpr int TILE_BYTES = BK * D * 2;            // 8192
     static constexpr int STAGE_BYTES = NTILE * TILE_BYTES;
     static constexpr int SO_BYTES = BK * D * 2;              // the Out tile, bf16
-    static constexpr size_t lds_bytes = (size_t)NS * STAGE_BYTES + SO_BYTES;   // 81920
+    static constexpr size_t lds_bytes = (size_t)NS * STAGE_BYTES + SO_BYTES;   // 81920 at NS = 3
 };
 
 __device__ __forceinline__ int dma_sw(int r) { return ((r << 1) | ((r >> 3) & 1)) & 15; }
 
-#define LA_WAIT_VM(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
+// wait until at most N vector-memory instructions of this wave are outstanding
 template <int N>
 __device__ __forceinline__ void la_wait_vm()
 {
-    static_assert(N == 0 || N == 4 || N == 6 || N == 8 || N == 10 || N == 12, "add the count");
-    if (N == 0) LA_WAIT_VM(0);
-    if (N == 4) LA_WAIT_VM(4);
-    if (N == 6) LA_WAIT_VM(6);
-    if (N == 8) LA_WAIT_VM(8);
-    if (N == 10) LA_WAIT_VM(10);
-    if (N == 12) LA_WAIT_VM(12);
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit field");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// ... at most n (a wave-uniform run-time value, n <= N): the count of the instruction is an
+// immediate, so pick the largest even one that does not exceed n
+template <int N>
+__device__ __forceinline__ void la_wait_vm_le(int n)
+{
+    if constexpr (N <= 0) {
+        la_wait_vm<0>();
+    } else {
+        if (n >= N) la_wait_vm<N>();
+        else la_wait_vm_le<N - 2>(n);
+    }
 }
 // LDS traffic of this wave complete, then the workgroup barrier; nothing moves across it
 #define LA_LDS_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
@@ -110,10 +122,10 @@ __device__ __forceinline__ U2 lds_read_tr(const unsigned char *p)
 // NT_STORE: the result stores carry the non-temporal hint (a template parameter because
 // two stores that differ only in the hint are merged into one plain store when they sit in
 // the two arms of a run-time branch).
-template <bool REV, bool NT_STORE, int ABL>
-__global__ __launch_bounds__(256, 2) void la_scan_bf16_dma(ScanLaunch launch, LaLambdas lams)
+template <bool REV, bool NT_STORE, int ABL, int NS_>
+__global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLaunch launch, LaLambdas lams)
 {
-    using Cfg = DmaCfg;
+    using Cfg = DmaCfg<NS_>;
     constexpr int D = Cfg::D, BK = Cfg::BK, NS = Cfg::NS, NTILE = Cfg::NTILE;
     constexpr int KS_D = D / 16;               // k-steps over the feature dim (8)
     constexpr int KS_B = BK / 16;              // k-steps over the block rows (2)
@@ -270,20 +282,16 @@ __global__ __launch_bounds__(256, 2) void la_scan_bf16_dma(ScanLaunch launch, La
         unsigned char *sb = smem_dma + stage * Cfg::STAGE_BYTES;
         // Every iteration issues the loads of block ib + PF, then (at its end) the 2 stores of
         // block ib.  Counting back from the youngest instruction, what may still be outstanding
-        // when block ib must have landed is PF - 1 times (stores, loads): the loads of blocks
-        // ib + 1 .. ib + PF - 1 with the stores between them.  At the start the loads of the
-        // first PF blocks were issued back to back (fewer stores in between), near the end
-        // some loads were never issued; short segments simply wait for everything.
+        // when block ib must have landed: the stores of the last PF - 1 blocks and the loads of
+        // blocks ib + 1 .. ib + PF - 1, as far as they exist (at the start the first PF blocks
+        // were issued back to back, with fewer stores among them; near the end some loads were
+        // never issued).  Short segments simply wait for everything.
         if (nblk < 2 * PF + 1 || ib + 1 >= nblk) {
             la_wait_vm<0>();
-        } else if constexpr (PF == 2) {
-            if (ib == 0) la_wait_vm<LOADS>();
-            else la_wait_vm<LOADS + ST>();
-        } else {                                // PF == 3
-            if (ib == 0) la_wait_vm<2 * LOADS>();
-            else if (ib == 1) la_wait_vm<2 * LOADS + ST>();
-            else if (ib + 2 < nblk) la_wait_vm<2 * (LOADS + ST)>();
-            else la_wait_vm<LOADS + ST>();      // ib == nblk - 2: the loads of one block are younger
+        } else {
+            const int young = min(PF - 1, nblk - 1 - ib);    // blocks whose loads are younger
+            const int olds = min(PF - 1, ib);                // blocks whose stores are younger
+            la_wait_vm_le<(PF - 1) * (LOADS + ST)>(LOADS * young + ST * olds);
         }
         if (t0 + BK > seg_hi) {                 // partial block: zero padding (exact)
             const U4 z = {0u, 0u, 0u, 0u};
@@ -529,11 +537,7 @@ __global__ __launch_bounds__(256, 2) void la_prepass_bf16_dma(ScanLaunch launch,
         const int t0 = seg_lo + blk * BK;
         unsigned char *sb = smem_dma + stage * Cfg::STAGE_BYTES;
         // younger than this block's loads: those of the next min(PF - 1, blocks left) blocks
-        const int ahead = min(PF - 1, nblk - 1 - ib);
-        if (ahead >= 3) la_wait_vm<3 * LOADS>();
-        else if (ahead == 2) la_wait_vm<2 * LOADS>();
-        else if (ahead == 1) la_wait_vm<LOADS>();
-        else la_wait_vm<0>();
+        la_wait_vm_le<(PF - 1) * LOADS>(LOADS * min(PF - 1, nblk - 1 - ib));
         if (t0 + BK > seg_hi) {                 // partial block: zero padding (exact)
             const U4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
