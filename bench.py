@@ -127,6 +127,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--point", type=int, default=0,
                     help="profiling aid: restrict the step to the sweep point with this n")
+    ap.add_argument("--sweep-only", action="store_true",
+                    help="profiling aid: only the sweep (headline, per-point figures, roofline); none of the "
+                         "side legs, so that a kernel trace holds the sweep's launches alone")
     ap.add_argument("--ablation", action="store_true",
                     help="measurement aid: instead of the benchmark, time the (32, 2048) and (1, 65536) points "
                          "with parts of the block scan left out or replaced (library debug switches) and "
@@ -288,190 +291,195 @@ def main():
     roofline["measured_stream_GBps"] = round(stream_gbs, 1)
     roofline["frac_of_measured_stream"] = round(achieved / stream_gbs, 4)
 
-    # ---- decode step (next row after the training path): B=8, H=32, d=128, bf16 ----------
-    # One token per (batch, head) streams the fp32 d x d state in and out: 2 * 4 d^2 bytes.
-    dB, dH = 8, 32
-    dlam = synth.workload("c4").lambdas
-    kv = torch.zeros(dB, dH, D, D, device=dev, dtype=torch.float32)
-    qkv = [(torch.randn(dB, dH, D, device=dev) * scale).to(torch.bfloat16) for _ in range(3)]
-    o1 = torch.empty_like(qkv[0])
-    for _ in range(10):
-        binding.la_decode_step(qkv[0], qkv[1], qkv[2], dlam, kv, o=o1)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    dsteps = 200
-    for _ in range(dsteps):
-        binding.la_decode_step(qkv[0], qkv[1], qkv[2], dlam, kv, o=o1)
-    e1.record()
-    e1.synchronize()
-    dec_ms = e0.elapsed_time(e1) / dsteps
-    dec_bytes = 2 * 4 * D * D * dB * dH
-    decode = {"workload": "la_decode_step, B=8, H=32, d=128, bf16 tokens, fp32 state in place",
-              "ms_per_step": round(dec_ms, 5), "tokens_per_s": round(dB / (dec_ms * 1e-3), 1),
-              "algorithmic_bytes_per_step": dec_bytes,
-              "achieved_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
-              "note": "includes launch overhead of one small kernel per step; 32 MiB of state per step"}
+    decode = gate_norm = swish_fused = lrpe = fp32_path = saved_states = other_configs = None
+    mfma_measured = None
+    if not args.sweep_only:
+        # ---- decode step (next row after the training path): B=8, H=32, d=128, bf16 ----------
+        # One token per (batch, head) streams the fp32 d x d state in and out: 2 * 4 d^2 bytes.
+        dB, dH = 8, 32
+        dlam = synth.workload("c4").lambdas
+        kv = torch.zeros(dB, dH, D, D, device=dev, dtype=torch.float32)
+        qkv = [(torch.randn(dB, dH, D, device=dev) * scale).to(torch.bfloat16) for _ in range(3)]
+        o1 = torch.empty_like(qkv[0])
+        for _ in range(10):
+            binding.la_decode_step(qkv[0], qkv[1], qkv[2], dlam, kv, o=o1)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        dsteps = 200
+        for _ in range(dsteps):
+            binding.la_decode_step(qkv[0], qkv[1], qkv[2], dlam, kv, o=o1)
+        e1.record()
+        e1.synchronize()
+        dec_ms = e0.elapsed_time(e1) / dsteps
+        dec_bytes = 2 * 4 * D * D * dB * dH
+        decode = {"workload": "la_decode_step, B=8, H=32, d=128, bf16 tokens, fp32 state in place",
+                  "ms_per_step": round(dec_ms, 5), "tokens_per_s": round(dB / (dec_ms * 1e-3), 1),
+                  "algorithmic_bytes_per_step": dec_bytes,
+                  "achieved_GBps": round(dec_bytes / (dec_ms * 1e-3) / 1e9, 1),
+                  "note": "includes launch overhead of one small kernel per step; 32 MiB of state per step"}
 
-    # ---- gated SRMSNorm output stage (next row): same tensors as the (1, 65536) point ---------
-    tg = views(1, TOKENS)
-    leg_min = {}
+        # ---- gated SRMSNorm output stage (next row): same tensors as the (1, 65536) point ---------
+        tg = views(1, TOKENS)
+        leg_min = {}
 
-    def _time(fn, it=20, key=None):
-        """Median of `it` single-call timings after 5 warm-up calls (the sweep's protocol); the
-        minimum is kept in `leg_min` under `key`."""
-        med, mn = per_iteration_ms(fn, warm=5, iters=it)
-        if key:
-            leg_min[key] = round(mn, 4)
-        return med
-    gf = _time(lambda: binding.la_gate_norm_fwd(tg["O"], tg["V"], 0.0, Y=tg["dQ"]), key="gate_norm_fwd")
-    gb = _time(lambda: binding.la_gate_norm_bwd(tg["O"], tg["V"], tg["dO"], 0.0, dO=tg["dK"], dU=tg["dV"]),
-               key="gate_norm_bwd")
-    tensor_bytes = 2 * numel
-    gate_norm = {"workload": "Y = SRMSNorm(O) * U and its backward, [1,16,65536,128] bf16",
-                 "fwd_ms": round(gf, 4), "bwd_ms": round(gb, 4),
-                 "fwd_ms_min": leg_min["gate_norm_fwd"], "bwd_ms_min": leg_min["gate_norm_bwd"],
-                 "fwd_GBps": round(3 * tensor_bytes / (gf * 1e-3) / 1e9, 1),
-                 "bwd_GBps": round(5 * tensor_bytes / (gb * 1e-3) / 1e9, 1),
-                 "note": "algorithmic bytes: 3 tensors forward, 5 backward; HBM-bound"}
+        def _time(fn, it=20, key=None):
+            """Median of `it` single-call timings after 5 warm-up calls (the sweep's protocol); the
+            minimum is kept in `leg_min` under `key`."""
+            med, mn = per_iteration_ms(fn, warm=5, iters=it)
+            if key:
+                leg_min[key] = round(mn, 4)
+            return med
+        gf = _time(lambda: binding.la_gate_norm_fwd(tg["O"], tg["V"], 0.0, Y=tg["dQ"]), key="gate_norm_fwd")
+        gb = _time(lambda: binding.la_gate_norm_bwd(tg["O"], tg["V"], tg["dO"], 0.0, dO=tg["dK"], dU=tg["dV"]),
+                   key="gate_norm_bwd")
+        tensor_bytes = 2 * numel
+        gate_norm = {"workload": "Y = SRMSNorm(O) * U and its backward, [1,16,65536,128] bf16",
+                     "fwd_ms": round(gf, 4), "bwd_ms": round(gb, 4),
+                     "fwd_ms_min": leg_min["gate_norm_fwd"], "bwd_ms_min": leg_min["gate_norm_bwd"],
+                     "fwd_GBps": round(3 * tensor_bytes / (gf * 1e-3) / 1e9, 1),
+                     "bwd_GBps": round(5 * tensor_bytes / (gb * 1e-3) / 1e9, 1),
+                     "note": "algorithmic bytes: 3 tensors forward, 5 backward; HBM-bound"}
 
-    # ---- Swish of the Q, K projections fused into the scans (next row) -------------------------
-    swish = []
-    for sB, sn in ((32, 2048), (1, TOKENS)):
-        t = views(sB, sn)
-        sf = _time(lambda: binding.la_fwd_swish(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=ws), key="sf")
-        sb = _time(lambda: binding.la_bwd_swish(t["Q"], t["K"], t["V"], lam, t["dO"], dQp=t["dQ"], dKp=t["dK"],
-                                                dV=t["dV"], workspace=ws), key="sb")
-        swish.append({"B": sB, "n": sn, "fwd_ms": round(sf, 4), "bwd_ms": round(sb, 4),
-                      "fwd_ms_min": leg_min["sf"], "bwd_ms_min": leg_min["sb"],
-                      "tokens_per_s": round(TOKENS / ((sf + sb) * 1e-3), 1),
-                      "algorithmic_GBps": round(16 * tensor_bytes / ((sf + sb) * 1e-3) / 1e9, 1)})
-    swish_fused = {"workload": "la_fwd_swish + la_bwd_swish, H=16, d=128, bf16, 65536 tokens",
-                   "points": swish,
-                   "note": "algorithmic bytes: 4 tensor passes forward, 12 backward (the two pre-activation "
-                           "tiles of the phi' epilogue are extra reads); separate activation kernels would "
-                           "add 10 passes to the plain path's 14"}
+        # ---- Swish of the Q, K projections fused into the scans (next row) -------------------------
+        swish = []
+        for sB, sn in ((32, 2048), (1, TOKENS)):
+            t = views(sB, sn)
+            sf = _time(lambda: binding.la_fwd_swish(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=ws), key="sf")
+            sb = _time(lambda: binding.la_bwd_swish(t["Q"], t["K"], t["V"], lam, t["dO"], dQp=t["dQ"], dKp=t["dK"],
+                                                    dV=t["dV"], workspace=ws), key="sb")
+            swish.append({"B": sB, "n": sn, "fwd_ms": round(sf, 4), "bwd_ms": round(sb, 4),
+                          "fwd_ms_min": leg_min["sf"], "bwd_ms_min": leg_min["sb"],
+                          "tokens_per_s": round(TOKENS / ((sf + sb) * 1e-3), 1),
+                          "algorithmic_GBps": round(16 * tensor_bytes / ((sf + sb) * 1e-3) / 1e9, 1)})
+        swish_fused = {"workload": "la_fwd_swish + la_bwd_swish, H=16, d=128, bf16, 65536 tokens",
+                       "points": swish,
+                       "note": "algorithmic bytes: 4 tensor passes forward, 12 backward (the two pre-activation "
+                               "tiles of the phi' epilogue are extra reads); separate activation kernels would "
+                               "add 10 passes to the plain path's 14"}
 
-    # ---- LRPE-d layer (next row): rotation + attention over 2d-wide query / key features ----------
-    lB, ln = 1, TOKENS
-    t = views(lB, ln)
-    theta = torch.rand((H, D), device=dev, dtype=torch.float32)
-    qw = torch.empty((lB, H, ln, 2 * D), device=dev, dtype=torch.bfloat16)
-    kw = torch.empty_like(qw)
-    dqw = torch.empty_like(qw)
-    dkw = torch.empty_like(qw)
-    dth = torch.zeros((H, D), device=dev, dtype=torch.float32)
-    lws = torch.empty(max(256, binding.la_lrpe_workspace_bytes(lB, H, ln, D)), dtype=torch.uint8, device=dev)
-    rot_f = _time(lambda: binding.la_lrpe_rotate_fwd(t["Q"], theta, Xw=qw))
-    binding.la_lrpe_rotate_fwd(t["K"], theta, Xw=kw)
-    rot_b = _time(lambda: binding.la_lrpe_rotate_bwd(t["Q"], theta, dqw, dX=t["dQ"], dtheta=dth, workspace=lws))
-    wf = _time(lambda: binding.la_fwd_wide(qw, kw, t["V"], lam, O=t["O"], workspace=ws))
-    wb = _time(lambda: binding.la_bwd_wide(qw, kw, t["V"], lam, t["dO"], dQw=dqw, dKw=dkw, dV=t["dV"], workspace=ws))
-    layer_ms = 2 * rot_f + wf + wb + 2 * rot_b
-    lrpe = {"workload": "LRPE-d attention layer, [1,16,65536,128] bf16: rotate Q and K (2d-wide features), "
-                        "la_fwd_wide, la_bwd_wide, rotation backward for Q and K (with the theta gradient)",
-            "rotate_fwd_ms": round(rot_f, 4), "rotate_bwd_ms": round(rot_b, 4),
-            "rotate_fwd_GBps": round(3 * tensor_bytes / (rot_f * 1e-3) / 1e9, 1),
-            "rotate_bwd_GBps": round(4 * tensor_bytes / (rot_b * 1e-3) / 1e9, 1),
-            "wide_fwd_ms": round(wf, 4), "wide_bwd_ms": round(wb, 4),
-            "layer_fwd_bwd_ms": round(layer_ms, 4),
-            "tokens_per_s": round(TOKENS / (layer_ms * 1e-3), 1),
-            "note": "wide attention = two accumulated scans over the cos and the sin half (twice the plain "
-                    "path's traffic plus the accumulator re-reads); rotation: 1 tensor in, 2 out (forward), "
-                    "3 in, 1 out (backward)"}
+        # ---- LRPE-d layer (next row): rotation + attention over 2d-wide query / key features ----------
+        lB, ln = 1, TOKENS
+        t = views(lB, ln)
+        theta = torch.rand((H, D), device=dev, dtype=torch.float32)
+        qw = torch.empty((lB, H, ln, 2 * D), device=dev, dtype=torch.bfloat16)
+        kw = torch.empty_like(qw)
+        dqw = torch.empty_like(qw)
+        dkw = torch.empty_like(qw)
+        dth = torch.zeros((H, D), device=dev, dtype=torch.float32)
+        lws = torch.empty(max(256, binding.la_lrpe_workspace_bytes(lB, H, ln, D)), dtype=torch.uint8, device=dev)
+        rot_f = _time(lambda: binding.la_lrpe_rotate_fwd(t["Q"], theta, Xw=qw))
+        binding.la_lrpe_rotate_fwd(t["K"], theta, Xw=kw)
+        rot_b = _time(lambda: binding.la_lrpe_rotate_bwd(t["Q"], theta, dqw, dX=t["dQ"], dtheta=dth, workspace=lws))
+        wf = _time(lambda: binding.la_fwd_wide(qw, kw, t["V"], lam, O=t["O"], workspace=ws))
+        wb = _time(lambda: binding.la_bwd_wide(qw, kw, t["V"], lam, t["dO"], dQw=dqw, dKw=dkw, dV=t["dV"], workspace=ws))
+        layer_ms = 2 * rot_f + wf + wb + 2 * rot_b
+        lrpe = {"workload": "LRPE-d attention layer, [1,16,65536,128] bf16: rotate Q and K (2d-wide features), "
+                            "la_fwd_wide, la_bwd_wide, rotation backward for Q and K (with the theta gradient)",
+                "rotate_fwd_ms": round(rot_f, 4), "rotate_bwd_ms": round(rot_b, 4),
+                "rotate_fwd_GBps": round(3 * tensor_bytes / (rot_f * 1e-3) / 1e9, 1),
+                "rotate_bwd_GBps": round(4 * tensor_bytes / (rot_b * 1e-3) / 1e9, 1),
+                "wide_fwd_ms": round(wf, 4), "wide_bwd_ms": round(wb, 4),
+                "layer_fwd_bwd_ms": round(layer_ms, 4),
+                "tokens_per_s": round(TOKENS / (layer_ms * 1e-3), 1),
+                "note": "wide attention = two accumulated scans over the cos and the sin half (twice the plain "
+                        "path's traffic plus the accumulator re-reads); rotation: 1 tensor in, 2 out (forward), "
+                        "3 in, 1 out (backward)"}
 
-    # ---- training step that keeps the forward workspace: la_fwd + la_bwd_saved, (1, 65536) point -----
-    t = views(1, TOKENS)
-    fws = torch.empty(max(256, binding.la_workspace_bytes(1, H, TOKENS, D, binding.LA_BF16, False)),
-                      dtype=torch.uint8, device=dev)
-    def train_step():
-        binding.la_fwd(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=fws)
-        binding.la_bwd_saved(t["Q"], t["K"], t["V"], lam, t["dO"], fws, dQ=t["dQ"], dK=t["dK"], dV=t["dV"],
-                             workspace=ws)
-    sv = _time(train_step, it=20, key="saved")
-    saved_states = {"workload": "la_fwd + la_bwd_saved (backward reuses the forward pass's segment states: the "
-                                "training-step form), [1,16,65536,128] bf16",
-                    "fwd_bwd_ms": round(sv, 4), "fwd_bwd_ms_min": leg_min["saved"],
-                    "tokens_per_s": round(TOKENS / (sv * 1e-3), 1),
-                    "plain_fwd_bwd_ms": sweep[-1]["fwd_bwd_ms"] if sweep[-1]["n"] == TOKENS else None,
-                    "note": "not the headline: la_bwd takes no saved context by contract"}
+        # ---- training step that keeps the forward workspace: la_fwd + la_bwd_saved, (1, 65536) point -----
+        t = views(1, TOKENS)
+        fws = torch.empty(max(256, binding.la_workspace_bytes(1, H, TOKENS, D, binding.LA_BF16, False)),
+                          dtype=torch.uint8, device=dev)
+        def train_step():
+            binding.la_fwd(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=fws)
+            binding.la_bwd_saved(t["Q"], t["K"], t["V"], lam, t["dO"], fws, dQ=t["dQ"], dK=t["dK"], dV=t["dV"],
+                                 workspace=ws)
+        sv = _time(train_step, it=20, key="saved")
+        saved_states = {"workload": "la_fwd + la_bwd_saved (backward reuses the forward pass's segment states: the "
+                                    "training-step form), [1,16,65536,128] bf16",
+                        "fwd_bwd_ms": round(sv, 4), "fwd_bwd_ms_min": leg_min["saved"],
+                        "tokens_per_s": round(TOKENS / (sv * 1e-3), 1),
+                        "plain_fwd_bwd_ms": sweep[-1]["fwd_bwd_ms"] if sweep[-1]["n"] == TOKENS else None,
+                        "note": "not the headline: la_bwd takes no saved context by contract"}
 
-    # ---- the other bf16 configurations (parity cases; timed here so that their rates come from the
-    # same run and protocol): C2 (TNL-400M-shaped layer, d = 64), C4 (TNL-7B-shaped layer), C5 (one
-    # 131072-token sequence, half of the heads without decay) ------------------------------------------
-    other_configs = []
-    for name in ("c2", "c4", "c5"):
-        w = synth.workload(name)
-        el = w.B * w.H * w.n * w.d
-        gsc = 1.0 / (w.d ** 0.5)
-        xs = [(torch.randn(el, generator=gen, device=dev, dtype=torch.float32) * gsc).to(torch.bfloat16)
-              .view(w.B, w.H, w.n, w.d) for _ in range(3)]
-        if name == "c4":                                     # Q, K = silu(N(0,1)) / sqrt(d)
-            for i in range(2):
-                xs[i] = (torch.nn.functional.silu(xs[i].float() / gsc) * gsc).to(torch.bfloat16)
-        xs.append(torch.randn(el, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
-                  .view(w.B, w.H, w.n, w.d))
-        outs = [torch.empty_like(xs[0]) for _ in range(4)]
-        need = binding.la_workspace_bytes(w.B, w.H, w.n, w.d, binding.LA_BF16, True)
-        cws = ws if need <= ws.numel() else torch.empty(need, dtype=torch.uint8, device=dev)
-        cf_ = lambda: binding.la_fwd(xs[0], xs[1], xs[2], w.lambdas, O=outs[0], workspace=cws)
-        cb_ = lambda: binding.la_bwd(xs[0], xs[1], xs[2], w.lambdas, xs[3], dQ=outs[1], dK=outs[2], dV=outs[3],
-                                     workspace=cws)
-        f_med, f_min = per_iteration_ms(cf_)
-        b_med, b_min = per_iteration_ms(cb_)
-        fb_med, fb_min = per_iteration_ms(lambda: (cf_(), cb_()))
-        tok = w.B * w.n
-        tps = tok / (fb_med * 1e-3)
-        bk, L, S = binding.la_plan(w.B, w.H, w.n, w.d, binding.LA_BF16)
-        mt = tps * w.H * 30 * w.d * w.d / 1e12
-        et = tps * w.H * executed_flops_per_token_head(w.d, bk) / 1e12
-        other_configs.append({
-            "config": name, "B": w.B, "H": w.H, "n": w.n, "d": w.d,
-            "fwd_ms": round(f_med, 4), "fwd_ms_min": round(f_min, 4), "bwd_ms": round(b_med, 4),
-            "bwd_ms_min": round(b_min, 4), "fwd_bwd_ms": round(fb_med, 4), "fwd_bwd_ms_min": round(fb_min, 4),
-            "tokens_per_s": round(tps, 1), "algorithmic_TBps": round(28 * w.d * w.H * tps / 1e12, 3),
-            "model_tflops": round(mt, 2), "pct_mfma_bf16_peak": round(100.0 * mt / MFMA_BF16_PEAK_TFLOPS, 2),
-            "executed_tflops": round(et, 2),
-            "pct_mfma_bf16_peak_executed": round(100.0 * et / MFMA_BF16_PEAK_TFLOPS, 2),
-            "block_len": bk, "segment_len": L, "segments": S})
-        del xs, outs, cws
-    torch.cuda.empty_cache()
+        # ---- the other bf16 configurations (parity cases; timed here so that their rates come from the
+        # same run and protocol): C2 (TNL-400M-shaped layer, d = 64), C4 (TNL-7B-shaped layer), C5 (one
+        # 131072-token sequence, half of the heads without decay) ------------------------------------------
+        other_configs = []
+        for name in ("c2", "c4", "c5"):
+            w = synth.workload(name)
+            el = w.B * w.H * w.n * w.d
+            gsc = 1.0 / (w.d ** 0.5)
+            xs = [(torch.randn(el, generator=gen, device=dev, dtype=torch.float32) * gsc).to(torch.bfloat16)
+                  .view(w.B, w.H, w.n, w.d) for _ in range(3)]
+            if name == "c4":                                     # Q, K = silu(N(0,1)) / sqrt(d)
+                for i in range(2):
+                    xs[i] = (torch.nn.functional.silu(xs[i].float() / gsc) * gsc).to(torch.bfloat16)
+            xs.append(torch.randn(el, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+                      .view(w.B, w.H, w.n, w.d))
+            outs = [torch.empty_like(xs[0]) for _ in range(4)]
+            need = binding.la_workspace_bytes(w.B, w.H, w.n, w.d, binding.LA_BF16, True)
+            cws = ws if need <= ws.numel() else torch.empty(need, dtype=torch.uint8, device=dev)
+            cf_ = lambda: binding.la_fwd(xs[0], xs[1], xs[2], w.lambdas, O=outs[0], workspace=cws)
+            cb_ = lambda: binding.la_bwd(xs[0], xs[1], xs[2], w.lambdas, xs[3], dQ=outs[1], dK=outs[2], dV=outs[3],
+                                         workspace=cws)
+            f_med, f_min = per_iteration_ms(cf_)
+            b_med, b_min = per_iteration_ms(cb_)
+            fb_med, fb_min = per_iteration_ms(lambda: (cf_(), cb_()))
+            tok = w.B * w.n
+            tps = tok / (fb_med * 1e-3)
+            bk, L, S = binding.la_plan(w.B, w.H, w.n, w.d, binding.LA_BF16)
+            mt = tps * w.H * 30 * w.d * w.d / 1e12
+            et = tps * w.H * executed_flops_per_token_head(w.d, bk) / 1e12
+            other_configs.append({
+                "config": name, "B": w.B, "H": w.H, "n": w.n, "d": w.d,
+                "fwd_ms": round(f_med, 4), "fwd_ms_min": round(f_min, 4), "bwd_ms": round(b_med, 4),
+                "bwd_ms_min": round(b_min, 4), "fwd_bwd_ms": round(fb_med, 4), "fwd_bwd_ms_min": round(fb_min, 4),
+                "tokens_per_s": round(tps, 1), "algorithmic_TBps": round(28 * w.d * w.H * tps / 1e12, 3),
+                "model_tflops": round(mt, 2), "pct_mfma_bf16_peak": round(100.0 * mt / MFMA_BF16_PEAK_TFLOPS, 2),
+                "executed_tflops": round(et, 2),
+                "pct_mfma_bf16_peak_executed": round(100.0 * et / MFMA_BF16_PEAK_TFLOPS, 2),
+                "block_len": bk, "segment_len": L, "segments": S})
+            del xs, outs, cws
+        torch.cuda.empty_cache()
 
-    # ---- what the matrix cores deliver with nothing in the way: the measured bf16 denominator -----
-    sink = torch.zeros(1, device=dev, dtype=torch.float32)
-    mf_iters, mf_wgs = 4000, 8 * 256
-    mf_flops = binding.debug_mfma_rate(mf_wgs, mf_iters, sink)
-    mf_med, mf_min = per_iteration_ms(lambda: binding.debug_mfma_rate(mf_wgs, mf_iters, sink), warm=3, iters=10)
-    mf_tflops = mf_flops / (mf_med * 1e-3) / 1e12
-    mfma_measured = {
-        "kernel": "register-only loop of v_mfma_f32_32x32x16_bf16, 4 independent accumulator tiles per wave, "
-                  "%d workgroups x 4 waves x %d iterations" % (mf_wgs, mf_iters),
-        "ms": round(mf_med, 4), "ms_min": round(mf_min, 4), "measured_tflops": round(mf_tflops, 1),
-        "published_tflops": MFMA_BF16_PEAK_TFLOPS,
-        "implied_clock_GHz": round(mf_tflops * 1e12 / (256 * 4 * 1024.0) / 1e9, 3),
-        "note": "implied clock = measured rate / (256 CUs x 4 SIMDs x 1024 flops per cycle), i.e. the clock at "
-                "which the published 2.5 PFLOP/s (at 2.4 GHz) scales to the measured rate",
-        "sweep_pct_of_measured_model_flops": None, "sweep_pct_of_measured_executed_flops": None}
+        # ---- what the matrix cores deliver with nothing in the way: the measured bf16 denominator -----
+        sink = torch.zeros(1, device=dev, dtype=torch.float32)
+        mf_iters, mf_wgs = 4000, 8 * 256
+        mf_flops = binding.debug_mfma_rate(mf_wgs, mf_iters, sink)
+        mf_med, mf_min = per_iteration_ms(lambda: binding.debug_mfma_rate(mf_wgs, mf_iters, sink), warm=3, iters=10)
+        mf_tflops = mf_flops / (mf_med * 1e-3) / 1e12
+        mfma_measured = {
+            "kernel": "register-only loop of v_mfma_f32_32x32x16_bf16, 4 independent accumulator tiles per wave, "
+                      "%d workgroups x 4 waves x %d iterations" % (mf_wgs, mf_iters),
+            "ms": round(mf_med, 4), "ms_min": round(mf_min, 4), "measured_tflops": round(mf_tflops, 1),
+            "published_tflops": MFMA_BF16_PEAK_TFLOPS,
+            "implied_clock_GHz": round(mf_tflops * 1e12 / (256 * 4 * 1024.0) / 1e9, 3),
+            "note": "implied clock = measured rate / (256 CUs x 4 SIMDs x 1024 flops per cycle), i.e. the clock at "
+                    "which the published 2.5 PFLOP/s (at 2.4 GHz) scales to the measured rate",
+            "sweep_pct_of_measured_model_flops": None, "sweep_pct_of_measured_executed_flops": None}
 
-    # ---- fp32 path (matrix-core fp32 kernel at d = 128): the (32, 2048) point in fp32 ---------------
-    fB, fn = 32, 2048
-    ft = {k: flat[k][: fB * H * fn * D].float().view(fB, H, fn, D) for k in ("Q", "K", "V", "dO")}
-    fo = [torch.empty_like(ft["Q"]) for _ in range(4)]
-    ff = _time(lambda: binding.la_fwd(ft["Q"], ft["K"], ft["V"], lam, O=fo[0]))
-    fb = _time(lambda: binding.la_bwd(ft["Q"], ft["K"], ft["V"], lam, ft["dO"], dQ=fo[1], dK=fo[2], dV=fo[3]))
-    f_tps = fB * fn / ((ff + fb) * 1e-3)
-    fp32_path = {"workload": "la_fwd + la_bwd in fp32, [32,16,2048,128]", "fwd_ms": round(ff, 4), "bwd_ms": round(fb, 4),
-                 "tokens_per_s": round(f_tps, 1),
-                 "model_tflops": round(f_tps * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12, 2),
-                 "executed_tflops": round(f_tps * H * (4 * (4 * 32 * D + 4 * D * D)) / 1e12, 2),
-                 "note": "compute-bound (fp32 MFMA peak 157.3 TFLOP/s); executed flops = four scans of "
-                         "4 BK d + 4 d^2 per token per head at BK = 32"}
-    del ft, fo
+        # ---- fp32 path (matrix-core fp32 kernel at d = 128): the (32, 2048) point in fp32 ---------------
+        fB, fn = 32, 2048
+        ft = {k: flat[k][: fB * H * fn * D].float().view(fB, H, fn, D) for k in ("Q", "K", "V", "dO")}
+        fo = [torch.empty_like(ft["Q"]) for _ in range(4)]
+        ff = _time(lambda: binding.la_fwd(ft["Q"], ft["K"], ft["V"], lam, O=fo[0]))
+        fb = _time(lambda: binding.la_bwd(ft["Q"], ft["K"], ft["V"], lam, ft["dO"], dQ=fo[1], dK=fo[2], dV=fo[3]))
+        f_tps = fB * fn / ((ff + fb) * 1e-3)
+        fp32_path = {"workload": "la_fwd + la_bwd in fp32, [32,16,2048,128]", "fwd_ms": round(ff, 4), "bwd_ms": round(fb, 4),
+                     "tokens_per_s": round(f_tps, 1),
+                     "model_tflops": round(f_tps * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12, 2),
+                     "executed_tflops": round(f_tps * H * (4 * (4 * 32 * D + 4 * D * D)) / 1e12, 2),
+                     "note": "compute-bound (fp32 MFMA peak 157.3 TFLOP/s); executed flops = four scans of "
+                             "4 BK d + 4 d^2 per token per head at BK = 32"}
+        del ft, fo
 
     total_tflops = value * H * MODEL_FLOPS_PER_TOKEN_HEAD / 1e12
     total_ex_tflops = value * H * executed_flops_per_token_head(D, sweep[0]["block_len"]) / 1e12
-    mfma_measured["sweep_pct_of_measured_model_flops"] = round(100.0 * total_tflops / mf_tflops, 2)
-    mfma_measured["sweep_pct_of_measured_executed_flops"] = round(100.0 * total_ex_tflops / mf_tflops, 2)
+    if mfma_measured:
+        mf_tflops = mfma_measured["measured_tflops"]
+        mfma_measured["sweep_pct_of_measured_model_flops"] = round(100.0 * total_tflops / mf_tflops, 2)
+        mfma_measured["sweep_pct_of_measured_executed_flops"] = round(100.0 * total_ex_tflops / mf_tflops, 2)
     # The target of north_star (>= 40 % of the bf16 MFMA peak at d = 128, 30 d^2 model flops) needs
     # 28 d bytes per token per head to move at this rate:
     target_tps = 0.40 * MFMA_BF16_PEAK_TFLOPS * 1e12 / (H * MODEL_FLOPS_PER_TOKEN_HEAD)

@@ -30,11 +30,13 @@
 //     10 %.)
 //
 // LDS tile layout: row r (0..31) at byte 256 r; its sixteen 16-byte chunks are stored at
-// chunk position c ^ sw(r), sw(r) = the low four bits of r rotated left by one.  A direct
+// chunk position c ^ sw(r), sw(r) = the low four bits of r rotated left by two.  A direct
 // load writes 64 lanes x 16 bytes to consecutive LDS addresses (4 rows); the swizzle is
 // applied on the global side, lane -> chunk (lane & 15) ^ sw(row).  With it the 16 lanes
-// of a ds_read_b128 group (16 rows, one chunk) and the 16 lanes of a transposing read
-// (4 rows x 32 bytes) each cover all banks exactly once.
+// of a ds_read_b128 group (16 rows, one chunk) cover sixteen different chunk positions, and
+// the 32 lanes of half a transposing read (4 rows x 64 bytes) cover all sixteen positions
+// twice over, once per 8-byte half: no bank is hit twice.  (With a rotation by one the
+// transposing reads still collided in pairs: 7 % of the kernel's cycles.)
 //
 // ds_read_b64_tr_b16, as measured: in each group of 16 lanes, lane i receives, as its four
 // 16-bit elements e = 0..3, element i % 4 of the 8 bytes that lane i / 4 + 4 e of the group
@@ -73,7 +75,7 @@ struct DmaCfg {
     static constexpr size_t lds_bytes = (size_t)NS * STAGE_BYTES + SO_BYTES;   // 81920 at NS = 3
 };
 
-__device__ __forceinline__ int dma_sw(int r) { return ((r << 1) | ((r >> 3) & 1)) & 15; }
+__device__ __forceinline__ int dma_sw(int r) { return ((r << 2) | ((r >> 2) & 3)) & 15; }
 
 // wait until at most N vector-memory instructions of this wave are outstanding
 template <int N>
@@ -186,7 +188,7 @@ __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLa
     // transposing reads: lane = (a4 + 4 b4) + 16 h16 + 32 g
     const int a4 = l & 3, b4 = (l >> 2) & 3, h16 = (l >> 4) & 1;
     const int tr_base = (4 * g + b4) * 256 + 8 * (a4 & 1);       // row 4g + b4, 8-byte half of the chunk
-    const int tr_sw = (2 * h16 + (a4 >> 1)) ^ (8 * g + 2 * b4);  // chunk within the 32 columns ^ sw(row), sel = 0
+    const int tr_sw = (2 * h16 + (a4 >> 1)) ^ (4 * b4 + g);      // chunk within the 32 columns ^ sw(row), sel = 0
     // direct loads: load slot ii = SPW w + j covers tile rows 4 ii .. 4 ii + 3
     int dma_row[SPW], dma_col[SPW];
 #pragma unroll
@@ -364,7 +366,7 @@ __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLa
         for (int ks = 0; ks < KS_B; ++ks) {
             const unsigned char *p = sC + tr_base + 16 * ks * 256;
             const U2 lo = lds_read_tr(p + ((((4 * w) ^ tr_sw)) << 4));
-            const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * w) ^ tr_sw ^ 1)) << 4));
+            const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * w) ^ tr_sw ^ 2)) << 4));
             cf[ks] = U4{lo[0], lo[1], hi[0], hi[1]};
         }
         // ---- P = bf16(S * mask) stays in registers: it is already the operand of the intra product
@@ -402,7 +404,7 @@ __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLa
             for (int ks = 0; ks < KS_B; ++ks) {
                 const unsigned char *p = sB + tr_base + 16 * ks * 256;
                 const U2 lo = lds_read_tr(p + ((((4 * mt) ^ tr_sw)) << 4));
-                const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * mt) ^ tr_sw ^ 1)) << 4));
+                const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * mt) ^ tr_sw ^ 2)) << 4));
                 bt[ks] = U4{lo[0], lo[1], hi[0], hi[1]};
             }
             LA_BATCH_FENCE();
@@ -500,7 +502,7 @@ __global__ __launch_bounds__(256, 2) void la_prepass_bf16_dma(ScanLaunch launch,
     }
     const int a4 = l & 3, b4 = (l >> 2) & 3, h16 = (l >> 4) & 1;
     const int tr_base = (4 * g + b4) * 256 + 8 * (a4 & 1);
-    const int tr_sw = (2 * h16 + (a4 >> 1)) ^ (8 * g + 2 * b4);
+    const int tr_sw = (2 * h16 + (a4 >> 1)) ^ (4 * b4 + g);
     int dma_row[2], dma_col[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -559,7 +561,7 @@ __global__ __launch_bounds__(256, 2) void la_prepass_bf16_dma(ScanLaunch launch,
         for (int ks = 0; ks < KS_B; ++ks) {
             const unsigned char *p = sC + tr_base + 16 * ks * 256;
             const U2 lo = lds_read_tr(p + ((((4 * w) ^ tr_sw)) << 4));
-            const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * w) ^ tr_sw ^ 1)) << 4));
+            const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * w) ^ tr_sw ^ 2)) << 4));
             const U4 cf = {lo[0], lo[1], hi[0], hi[1]};
 #pragma unroll
             for (int e = 0; e < 4; ++e)
@@ -573,7 +575,7 @@ __global__ __launch_bounds__(256, 2) void la_prepass_bf16_dma(ScanLaunch launch,
             for (int ks = 0; ks < KS_B; ++ks) {
                 const unsigned char *p = sB + tr_base + 16 * ks * 256;
                 const U2 lo = lds_read_tr(p + ((((4 * mt) ^ tr_sw)) << 4));
-                const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * mt) ^ tr_sw ^ 1)) << 4));
+                const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * mt) ^ tr_sw ^ 2)) << 4));
                 bt[ks] = U4{lo[0], lo[1], hi[0], hi[1]};
             }
             LA_BATCH_FENCE();
