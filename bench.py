@@ -91,6 +91,7 @@ def ablation(binding, torch, views, lam, ws):
         return round(0.5 * (ms[9] + ms[10]), 4)
 
     cases = [("default (direct-to-LDS scan, 32-row blocks, non-temporal result stores)", {}),
+             ("la_bwd as a dQ launch + a paired dK/dV launch (not one launch of three roles)", {"no_trio": 1}),
              ("register-staged scan and pre-pass (64-row blocks)", {"staged_scan": 1}),
              ("register-staged pre-pass only", {"staged_prepass": 1}),
              ("ordinary result stores", {"store_policy": 2}),
@@ -130,6 +131,9 @@ def main():
     ap.add_argument("--sweep-only", action="store_true",
                     help="profiling aid: only the sweep (headline, per-point figures, roofline); none of the "
                          "side legs, so that a kernel trace holds the sweep's launches alone")
+    ap.add_argument("--debug-switch", action="append", default=[], metavar="NAME=VALUE",
+                    help="measurement aid: set a debug switch of the library (csrc/la_debug.h) for the whole "
+                         "run, e.g. trio=0; may be given several times; recorded in the JSON line")
     ap.add_argument("--ablation", action="store_true",
                     help="measurement aid: instead of the benchmark, time the (32, 2048) and (1, 65536) points "
                          "with parts of the block scan left out or replaced (library debug switches) and "
@@ -153,6 +157,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     binding.load_library()
+    for kv in args.debug_switch:
+        name, val = kv.split("=", 1)
+        binding.debug_set(name, int(val))
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     lam = synth.workload("c3_2048").lambdas
@@ -263,14 +270,14 @@ def main():
     scan_ms, launches = binding.la_profile_collect()
     binding.la_profile_enable(False)
     # Algorithmic bytes of the block-scan launches of one fwd+bwd at one sweep point:
-    # O = scan(Q,K,V) and dQ = scan(dO,V,K) each read 3 and write 1 tensor; the paired
-    # dK/dV launch reads Q,K,V,dO once and writes 2: (4 + 4 + 6) * d * 2 B = 28 d bytes
-    # per token per head.
+    # O = scan(Q,K,V) and dQ = scan(dO,V,K) each read 3 and write 1 tensor; the dK / dV
+    # pair reads Q,K,V,dO once and writes 2: (4 + 4 + 6) * d * 2 B = 28 d bytes per token
+    # per head, in two launches (la_fwd's scan; la_bwd's dQ, dK, dV scans as one).
     alg_bytes_per_point = 28 * D * H * TOKENS
     alg_bytes = alg_bytes_per_point * len(POINTS) * args.steps
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
     per_launch = alg_bytes / max(launches, 1)
-    roofline = {"bound": "hbm", "kernel": "la_scan_bf16_dma (block scan, d=128: fwd, dQ, paired dK/dV launches)",
+    roofline = {"bound": "hbm", "kernel": "la_scan_bf16_dma (block scan, d=128: la_fwd's launch and la_bwd's three-role launch)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic_note(),
                 "launches": launches, "avg_launch_ms": round(scan_ms / max(launches, 1), 5),
@@ -498,6 +505,7 @@ def main():
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "debug_switches": args.debug_switch,
         "config": {"workload": ("" if not args.point else "PROFILING SUBSET n=%d of: " % args.point) +
                                "c3 sweep: (B,n) in {(32,2048),(16,4096),(8,8192),(4,16384),(2,32768),"
                                "(1,65536)}, H=16, d=128, lambda_h geometric in [0.9,0.9999]; one step = "

@@ -55,6 +55,7 @@ struct Switches {
     std::atomic<long> f32_plain{0};      // != 0: fp32 at d = 128 runs the FMA kernel
     std::atomic<long> store_policy{0};   // direct-to-LDS scan: 2 = ordinary instead of non-temporal result stores
     std::atomic<long> staged_prepass{0}; // != 0: bf16 at d = 128 runs the register-staged segment-state pre-pass
+    std::atomic<long> no_trio{0};        // != 0: la_bwd's direct-to-LDS block scans as a dQ launch and a paired dK / dV launch
     std::atomic<long> ablate{0};         // 1..3: measurement-only variants of the direct-to-LDS scan
     std::atomic<long> staged_scan{0};    // != 0: bf16 at d = 128 runs the register-staged block scan
                                          // (64-row blocks) instead of the direct-to-LDS one (32-row)
@@ -69,6 +70,7 @@ std::atomic<long> *find_switch(const char *name)
     if (!std::strcmp(name, "f32_plain")) return &g_sw.f32_plain;
     if (!std::strcmp(name, "staged_scan")) return &g_sw.staged_scan;
     if (!std::strcmp(name, "ablate")) return &g_sw.ablate;
+    if (!std::strcmp(name, "no_trio")) return &g_sw.no_trio;
     if (!std::strcmp(name, "staged_prepass")) return &g_sw.staged_prepass;
     if (!std::strcmp(name, "store_policy")) return &g_sw.store_policy;
     return nullptr;
@@ -210,6 +212,20 @@ hipError_t launch_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s
     // paired launch: two workgroups per item, items padded to a multiple of the 8 XCDs
     const unsigned wgs = a.nroles == 2 ? 2u * (unsigned)((a.items + 7) / 8 * 8) : (unsigned)a.items;
     dim3 grid(wgs), block(Cfg::NT);
+    hipLaunchKernelGGL(kern, grid, block, Cfg::lds_bytes, s, a, lams);
+    return hipGetLastError();
+}
+
+// The backward pass's three block scans in one launch (see the kernel).
+hipError_t launch_bf16_dma_trio(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
+{
+    using Cfg = DmaCfg<3>;
+    auto kern = la_scan_bf16_dma<false, true, 0, 3, true>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
+    if (attr_err != hipSuccess) return attr_err;
+    dim3 grid(3u * (unsigned)((a.items + 7) / 8 * 8)), block(Cfg::NT);
     hipLaunchKernelGGL(kern, grid, block, Cfg::lds_bytes, s, a, lams);
     return hipGetLastError();
 }
@@ -379,7 +395,7 @@ ScanArgs make_args(const void *A, const void *Bm, const void *C, void *Out, cons
 int run_prepass(const ScanArgs *a, int nroles, const LaLambdas &lams, long scans, int d, la_dtype dt,
                 hipStream_t s)
 {
-    ScanLaunch l;
+    ScanLaunch l = {};
     l.r[0] = a[0]; l.r[1] = a[nroles - 1]; l.nroles = nroles; l.items = (int)(scans * a[0].S);
     return launch_scan_kernel<false, true>(l, lams, d, dt, s) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
 }
@@ -414,7 +430,7 @@ int run_segment_scan_pair(const ScanArgs &f, const ScanArgs &r, const LaLambdas 
 template <bool REV>
 int run_block_scan(const ScanArgs &a, const LaLambdas &lams, long scans, int d, la_dtype dt, hipStream_t s)
 {
-    ScanLaunch l;
+    ScanLaunch l = {};
     l.r[0] = a; l.r[1] = a; l.nroles = 1; l.items = (int)(scans * a.S);
     ScopedTimer t(s);
     return launch_scan_kernel<REV, false>(l, lams, d, dt, s) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
@@ -460,7 +476,7 @@ int run_scan(const void *A, const void *Bm, const void *C, void *Out, const LaLa
 int run_reverse_pair(const ScanArgs &ak, const ScanArgs &av, const LaLambdas &lams, long scans,
                      int d, la_dtype dt, hipStream_t s)
 {
-    ScanLaunch l;
+    ScanLaunch l = {};
     l.items = (int)(scans * ak.S);
     const bool pair = dt == LA_BF16 && g_sw.no_pair.load(std::memory_order_relaxed) == 0;
     if (pair) {
@@ -525,6 +541,14 @@ int run_backward(const void *Q, const void *K, const void *V, const void *dO, vo
             if (rc == LA_OK) rc = run_segment_scan_pair(pre[0], pre[1], lams, scans, d, s);
         }
         if (rc != LA_OK) return rc;
+    }
+    if (!g_sw.no_trio.load(std::memory_order_relaxed) && dt == LA_BF16 && d == 128 &&
+        !(pre[0].act | pre[1].act | av.act) && !g_sw.staged_scan.load(std::memory_order_relaxed) &&
+        !g_sw.no_pair.load(std::memory_order_relaxed) && !g_sw.ablate.load(std::memory_order_relaxed)) {
+        ScanLaunch l;
+        l.r[0] = pre[0]; l.r[1] = pre[1]; l.r[2] = av; l.nroles = 3; l.items = (int)(scans * p.S);
+        ScopedTimer t(s);
+        return launch_bf16_dma_trio(l, lams, s) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
     }
     int rc = run_block_scan<false>(pre[0], lams, scans, d, dt, s);
     if (rc != LA_OK) return rc;

@@ -106,8 +106,10 @@ __device__ __forceinline__ float la_swish_grad(float x)
 // XCD's L2.  Workgroup ids go round-robin over the 8 XCDs:
 //   xcd = id % 8, slot = id / 8, role = slot % 2, item = (slot / 2) * 8 + xcd.
 struct ScanLaunch {
-    ScanArgs r[2];
-    int nroles;          // 1 or 2
+    ScanArgs r[3];
+    int nroles;          // 1, 2, or 3 = the whole backward pass in one launch of the direct-to-LDS block
+                         // scan: r[0] forward in time (dQ), r[1] and r[2] reversed (dK, dV), the three
+                         // workgroups of an item on one XCD (id % 8), roles in consecutive slots
     int items;           // scans * S
 };
 

@@ -20,6 +20,8 @@
  *                    3: arithmetic only); their results are wrong by design
  *   "staged_prepass" != 0: bf16 at d = 128 runs the register-staged segment-state pre-pass
  *                    instead of the direct-to-LDS one
+ *   "no_trio"        != 0: la_bwd runs its direct-to-LDS block scans as a dQ launch followed by a
+ *                    paired dK / dV launch instead of one launch of three roles
  *   "store_policy"   2: the direct-to-LDS block scan stores its results with ordinary instead
  *                    of non-temporal stores
  *   "staged_scan"    != 0: bf16 at d = 128 runs the register-staged block scan (64-row

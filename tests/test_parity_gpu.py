@@ -429,3 +429,9 @@ def test_direct_to_lds_and_register_staged_block_scans_agree():
         for a, b in zip(direct, staged):
             assert oracle.rel_max_err(a, b) <= 1e-2
             assert not np.array_equal(a, b)
+        # the backward pass's block scans as two launches (dQ, then the dK / dV pair) instead of one
+        # launch of three roles: the same instructions on the same data, so the same bits
+        with binding.debug(no_trio=1):
+            split = _run_gpu(w, xs, lseg=lseg)
+        for a, b in zip(direct, split):
+            assert np.array_equal(a, b)
