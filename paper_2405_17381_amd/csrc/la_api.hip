@@ -266,10 +266,11 @@ hipError_t launch_bf16_dma(const ScanLaunch &a, const LaLambdas &lams, hipStream
               : launch_bf16_dma_variant<REV, false, 0>(a, lams, s);
 }
 
+template <int NS>
 hipError_t launch_prepass_bf16_dma(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
-    using Cfg = DmaPrepassCfg;
-    auto kern = la_prepass_bf16_dma;
+    using Cfg = DmaPrepassCfg<NS>;
+    auto kern = la_prepass_bf16_dma<NS>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
@@ -333,7 +334,7 @@ hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
             if (d == 64) return launch_prepass_bf16<64, false>(a, lams, s);
             if (g_sw.staged_scan.load(std::memory_order_relaxed) || g_sw.staged_prepass.load(std::memory_order_relaxed))
                 return launch_prepass_bf16<128, false>(a, lams, s);
-            return launch_prepass_bf16_dma(a, lams, s);
+            return launch_prepass_bf16_dma<5>(a, lams, s);
         }
         if (act) return d == 64 ? launch_bf16<64, REV, true>(a, lams, s) : launch_bf16<128, REV, true>(a, lams, s);
         if (d == 64) return launch_bf16<64, REV, false>(a, lams, s);

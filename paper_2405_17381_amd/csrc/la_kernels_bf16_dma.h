@@ -456,21 +456,23 @@ __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLa
 // The local end state of every segment (see la_kernels_prepass.h for what it is and how the
 // launch is laid out: roles, head order, decay cut-off), computed as the state update of the
 // block scan alone: per 32-row block the Bm and C tiles arrive by direct loads (2 x 8 KB per
-// stage, five stages: four blocks of prefetch, so that the short per-block chain of a slowly
-// decaying head never waits for memory), Bm^T and this wave's C fragments come from the
+// stage, five stages: four blocks of prefetch; two or eight blocks change its time by 6 %
+// either way), Bm^T and this wave's C fragments come from the
 // transposing reads, and the decay is folded into the weights put on the C fragments (row r
 // of block k is weighted by its full distance to the segment's far end), so the accumulator
 // is never rescaled.  One barrier per block, no stores until the state is written out.
+template <int NS_>
 struct DmaPrepassCfg {
-    static constexpr int D = 128, BK = 32, NS = 5, NT = 256;
+    static constexpr int D = 128, BK = 32, NS = NS_, NT = 256;
     static constexpr int TILE_BYTES = BK * D * 2;
     static constexpr int STAGE_BYTES = 2 * TILE_BYTES;       // Bm, C
     static constexpr size_t lds_bytes = (size_t)NS * STAGE_BYTES;   // 81920
 };
 
+template <int NS_>
 __global__ __launch_bounds__(256, 2) void la_prepass_bf16_dma(ScanLaunch launch, LaLambdas lams)
 {
-    using Cfg = DmaPrepassCfg;
+    using Cfg = DmaPrepassCfg<NS_>;
     constexpr int D = Cfg::D, BK = Cfg::BK, NS = Cfg::NS, PF = NS - 1;
     constexpr int KS_B = BK / 16, MT_D = D / 32;
     constexpr int LOADS = 4;                   // direct loads per wave and block (2 tiles x 2 slots)
@@ -570,32 +572,42 @@ __global__ __launch_bounds__(256, 2) void la_prepass_bf16_dma(ScanLaunch launch,
         const unsigned char *sB = sb, *sC = sb + Cfg::TILE_BYTES;
         // distance of this block to the segment's far end, folded into the weights
         const float mu = rev ? pw(blk * BK) : pw((nblk - 1 - blk) * BK);
-        U4 cw[KS_B];
+        // All twenty transposing reads of the block are issued before anything waits for them:
+        // a slowly decaying head's workgroup is often alone on its compute unit, and with one
+        // wave per SIMD every exposed LDS latency is paid in full.
+        U2 rc[KS_B][2], rb[MT_D][KS_B][2];
 #pragma unroll
         for (int ks = 0; ks < KS_B; ++ks) {
             const unsigned char *p = sC + tr_base + 16 * ks * 256;
-            const U2 lo = lds_read_tr(p + ((((4 * w) ^ tr_sw)) << 4));
-            const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * w) ^ tr_sw ^ 2)) << 4));
-            const U4 cf = {lo[0], lo[1], hi[0], hi[1]};
+            rc[ks][0] = lds_read_tr(p + ((((4 * w) ^ tr_sw)) << 4));
+            rc[ks][1] = lds_read_tr(p + 8 * 256 + ((((4 * w) ^ tr_sw ^ 2)) << 4));
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT_D; ++mt)
+#pragma unroll
+            for (int ks = 0; ks < KS_B; ++ks) {
+                const unsigned char *p = sB + tr_base + 16 * ks * 256;
+                rb[mt][ks][0] = lds_read_tr(p + ((((4 * mt) ^ tr_sw)) << 4));
+                rb[mt][ks][1] = lds_read_tr(p + 8 * 256 + ((((4 * mt) ^ tr_sw ^ 2)) << 4));
+            }
+        LA_BATCH_FENCE();
+        U4 cw[KS_B];
+#pragma unroll
+        for (int ks = 0; ks < KS_B; ++ks) {
+            const U4 cf = {rc[ks][0][0], rc[ks][0][1], rc[ks][1][0], rc[ks][1][1]};
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 cw[ks][e] = pack2_bf16(bf16_lo(cf[e]) * (wt[8 * ks + 2 * e] * mu),
                                        bf16_hi(cf[e]) * (wt[8 * ks + 2 * e + 1] * mu));
         }
+        // four independent accumulator chains, interleaved
 #pragma unroll
-        for (int mt = 0; mt < MT_D; ++mt) {
-            U4 bt[KS_B];
+        for (int ks = 0; ks < KS_B; ++ks)
 #pragma unroll
-            for (int ks = 0; ks < KS_B; ++ks) {
-                const unsigned char *p = sB + tr_base + 16 * ks * 256;
-                const U2 lo = lds_read_tr(p + ((((4 * mt) ^ tr_sw)) << 4));
-                const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * mt) ^ tr_sw ^ 2)) << 4));
-                bt[ks] = U4{lo[0], lo[1], hi[0], hi[1]};
+            for (int mt = 0; mt < MT_D; ++mt) {
+                const U4 bt = {rb[mt][ks][0][0], rb[mt][ks][0][1], rb[mt][ks][1][0], rb[mt][ks][1][1]};
+                st[mt] = mfma32(bt, cw[ks], st[mt]);
             }
-            LA_BATCH_FENCE();
-#pragma unroll
-            for (int ks = 0; ks < KS_B; ++ks) st[mt] = mfma32(bt[ks], cw[ks], st[mt]);
-        }
         stage = stage + 1 < NS ? stage + 1 : 0;
     }
 
