@@ -380,6 +380,13 @@ def main():
         rot_b = _time(lambda: binding.la_lrpe_rotate_bwd(t["Q"], theta, dqw, dX=t["dQ"], dtheta=dth, workspace=lws))
         wf = _time(lambda: binding.la_fwd_wide(qw, kw, t["V"], lam, O=t["O"], workspace=ws))
         wb = _time(lambda: binding.la_bwd_wide(qw, kw, t["V"], lam, t["dO"], dQw=dqw, dKw=dkw, dV=t["dV"], workspace=ws))
+        # forward with the non-square state in one kernel (whole sequences only) against the two
+        # accumulated scans, at the (32, 2048) shape
+        tw = views(32, 2048)
+        qw2, kw2 = qw.view(32, H, 2048, 2 * D), kw.view(32, H, 2048, 2 * D)
+        wf_one = _time(lambda: binding.la_fwd_wide(qw2, kw2, tw["V"], lam, O=tw["O"], workspace=ws))
+        with binding.debug(wide_slices=1):
+            wf_two = _time(lambda: binding.la_fwd_wide(qw2, kw2, tw["V"], lam, O=tw["O"], workspace=ws))
         layer_ms = 2 * rot_f + wf + wb + 2 * rot_b
         lrpe = {"workload": "LRPE-d attention layer, [1,16,65536,128] bf16: rotate Q and K (2d-wide features), "
                             "la_fwd_wide, la_bwd_wide, rotation backward for Q and K (with the theta gradient)",
@@ -387,6 +394,8 @@ def main():
                 "rotate_fwd_GBps": round(3 * tensor_bytes / (rot_f * 1e-3) / 1e9, 1),
                 "rotate_bwd_GBps": round(4 * tensor_bytes / (rot_b * 1e-3) / 1e9, 1),
                 "wide_fwd_ms": round(wf, 4), "wide_bwd_ms": round(wb, 4),
+                "wide_fwd_ms_32x2048_single_kernel": round(wf_one, 4),
+                "wide_fwd_ms_32x2048_two_accumulated_scans": round(wf_two, 4),
                 "layer_fwd_bwd_ms": round(layer_ms, 4),
                 "tokens_per_s": round(TOKENS / (layer_ms * 1e-3), 1),
                 "note": "wide attention = two accumulated scans over the cos and the sin half (twice the plain "

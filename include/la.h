@@ -240,8 +240,11 @@ int la_bwd_swish(const void *Qp, const void *Kp, const void *V,
  * and its gradients.  Qw, Kw, dQw, dKw: [B, H, n, dk]; V, O, dO, dV: [B, H, n, dv];
  * dv is 64 or 128.  The scores add over the m slices of dv features, so the result
  * is accumulated over m scans of slices (the KV state is m states of dv x dv); O and
- * dV are read back and rounded to dt between slices.  Workspace as la_fwd / la_bwd
- * with d = dv.  The rotation itself (and theta's gradient) is the caller's.
+ * dV are read back and rounded to dt between slices.  Exception: la_fwd_wide in bf16 with
+ * dk = 256, dv = 128 on a problem the planner does not cut into segments
+ * (la_workspace_bytes(B, H, n, dv, dt, 0) == 0) runs ONE kernel that holds the whole
+ * 256 x 128 state: one pass over Qw, Kw, V, no intermediate rounding of O.  Workspace as
+ * la_fwd / la_bwd with d = dv.  The rotation itself (and theta's gradient) is the caller's.
  */
 int la_fwd_wide(const void *Qw, const void *Kw, const void *V,
                 const float *lambda /* host, [H] */,

@@ -12,6 +12,7 @@
 #include "la_debug.h"
 #include "la_kernels_bf16.h"
 #include "la_kernels_bf16_dma.h"
+#include "la_kernels_bf16_dma_wide.h"
 #include "la_kernels_f32.h"
 #include "la_kernels_f32m.h"
 #include "la_kernels_gate.h"
@@ -56,6 +57,7 @@ struct Switches {
     std::atomic<long> store_policy{0};   // direct-to-LDS scan: 2 = ordinary instead of non-temporal result stores
     std::atomic<long> staged_prepass{0}; // != 0: bf16 at d = 128 runs the register-staged segment-state pre-pass
     std::atomic<long> no_trio{0};        // != 0: la_bwd's direct-to-LDS block scans as a dQ launch and a paired dK / dV launch
+    std::atomic<long> wide_slices{0};    // != 0: la_fwd_wide always runs accumulated scans over d_v-wide slices
     std::atomic<long> ablate{0};         // 1..3: measurement-only variants of the direct-to-LDS scan
     std::atomic<long> staged_scan{0};    // != 0: bf16 at d = 128 runs the register-staged block scan
                                          // (64-row blocks) instead of the direct-to-LDS one (32-row)
@@ -70,6 +72,7 @@ std::atomic<long> *find_switch(const char *name)
     if (!std::strcmp(name, "f32_plain")) return &g_sw.f32_plain;
     if (!std::strcmp(name, "staged_scan")) return &g_sw.staged_scan;
     if (!std::strcmp(name, "ablate")) return &g_sw.ablate;
+    if (!std::strcmp(name, "wide_slices")) return &g_sw.wide_slices;
     if (!std::strcmp(name, "no_trio")) return &g_sw.no_trio;
     if (!std::strcmp(name, "staged_prepass")) return &g_sw.staged_prepass;
     if (!std::strcmp(name, "store_policy")) return &g_sw.store_policy;
@@ -747,6 +750,27 @@ int la_fwd_wide(const void *Qw, const void *Kw, const void *V, const float *lamb
     if (rc == LA_OK) rc = check_wide(dk, dv);
     if (rc != LA_OK) return rc;
     if (!Qw || !Kw) return LA_ERR_NULL;
+    // d_k = 256, d_v = 128 in bf16, whole sequences: one kernel with the 256 x 128 state
+    if (dt == LA_BF16 && dk == 256 && dv == 128 && make_plan(B, H, n, dv, dt).S == 1 &&
+        !g_sw.wide_slices.load(std::memory_order_relaxed)) {
+        if (!V || !O || !lambda) return LA_ERR_NULL;
+        if (!aligned16(Qw) || !aligned16(Kw) || !aligned16(V) || !aligned16(O)) return LA_ERR_ALIGN;
+        LaLambdas lams;
+        rc = check_lambda(lambda, H, &lams);
+        if (rc != LA_OK) return rc;
+        Plan p = make_plan(B, H, n, dv, dt);
+        ScanLaunch l = {};
+        l.r[0] = make_args(Qw, Kw, V, O, p, H, n, dv, dt, nullptr, 0);
+        l.nroles = 1; l.items = B * H;
+        auto kern = la_scan_bf16_dma_wide;
+        static std::once_flag once;
+        static hipError_t attr_err = hipSuccess;
+        std::call_once(once, [&] { attr_err = allow_lds(kern, DmaWideCfg::lds_bytes); });
+        if (attr_err != hipSuccess) return LA_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3((unsigned)(B * H)), dim3(DmaWideCfg::NT), DmaWideCfg::lds_bytes,
+                           (hipStream_t)hip_stream, l, lams);
+        return hipGetLastError() == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+    }
     const size_t esz = dt == LA_BF16 ? 2 : 4;
     for (int j = 0; j < dk / dv; ++j) {
         Variant var;

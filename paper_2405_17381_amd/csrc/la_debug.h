@@ -22,6 +22,8 @@
  *                    instead of the direct-to-LDS one
  *   "no_trio"        != 0: la_bwd runs its direct-to-LDS block scans as a dQ launch followed by a
  *                    paired dK / dV launch instead of one launch of three roles
+ *   "wide_slices"    != 0: la_fwd_wide always runs accumulated scans over d_v-wide slices, also where
+ *                    the single kernel with the non-square state applies
  *   "store_policy"   2: the direct-to-LDS block scan stores its results with ordinary instead
  *                    of non-temporal stores
  *   "staged_scan"    != 0: bf16 at d = 128 runs the register-staged block scan (64-row
