@@ -113,6 +113,9 @@ struct ScanLaunch {
     int items;           // scans * S
 };
 
+// kernel arguments travel in the dispatch packet: 4 KB at most
+static_assert(sizeof(ScanLaunch) + sizeof(LaLambdas) <= 4096, "kernel arguments exceed the 4 KB limit");
+
 // Segment scan over local segment states, in place:
 //   forward: W[s] <- state entering segment s  (W[0] <- carried-in state or 0)
 //   reverse: W[s] <- state entering segment s from the right (W[S-1] <- 0)

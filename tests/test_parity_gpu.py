@@ -115,6 +115,26 @@ def test_bf16_ragged_and_segmented(d, n, lseg):
     _full_case(w, lseg)
 
 
+@pytest.mark.parametrize("n", [31, 32, 33, 95, 96, 97, 129])
+def test_bf16_d128_block_edges_of_the_direct_to_lds_kernels(n):
+    """Sequence lengths around multiples of the 32-row block of the direct-to-LDS kernels (partial
+    last block of the forward scan = partial first block of the reverse scans), whole and cut."""
+    lam = [1.0, 0.999, 0.9, 0.3]
+    w = synth.custom(3, len(lam), n, 128, lam, seed=3100 + n, dtype="bf16")
+    _full_case(w)
+    if n > 64:
+        _full_case(w, lseg=64)
+
+
+def test_maximum_head_count_d128():
+    """256 heads at d = 128: the backward pass's three-role launch carries three argument sets and
+    the table of 256 decay rates in one dispatch packet."""
+    H = 256
+    lam = [float(0.5 + 0.5 * (h / (H - 1))) for h in range(H)]
+    w = synth.custom(1, H, 100, 128, lam, seed=322, dtype="bf16")
+    _full_case(w)
+
+
 def test_c2_bf16_d64_full():
     _full_case(synth.workload("c2"))
     _full_case(synth.workload("c2"), lseg=512)
