@@ -56,9 +56,10 @@ struct Switches {
     std::atomic<long> f32_plain{0};      // != 0: fp32 at d = 128 runs the FMA kernel
     std::atomic<long> store_policy{0};   // direct-to-LDS scan: 2 = ordinary instead of non-temporal result stores
     std::atomic<long> staged_prepass{0}; // != 0: bf16 at d = 128 runs the register-staged segment-state pre-pass
+    std::atomic<long> prepass_groups{0}; // 1, 2: wave groups per workgroup of the direct-to-LDS pre-pass (own choice: 4)
     std::atomic<long> no_trio{0};        // != 0: la_bwd's direct-to-LDS block scans as a dQ launch and a paired dK / dV launch
     std::atomic<long> wide_slices{0};    // != 0: la_fwd_wide always runs accumulated scans over d_v-wide slices
-    std::atomic<long> ablate{0};         // 1..3: measurement-only variants of the direct-to-LDS scan
+    std::atomic<long> ablate{0};         // 1..4: measurement-only variants of the direct-to-LDS scan
     std::atomic<long> staged_scan{0};    // != 0: bf16 at d = 128 runs the register-staged block scan
                                          // (64-row blocks) instead of the direct-to-LDS one (32-row)
 } g_sw;
@@ -75,6 +76,7 @@ std::atomic<long> *find_switch(const char *name)
     if (!std::strcmp(name, "wide_slices")) return &g_sw.wide_slices;
     if (!std::strcmp(name, "no_trio")) return &g_sw.no_trio;
     if (!std::strcmp(name, "staged_prepass")) return &g_sw.staged_prepass;
+    if (!std::strcmp(name, "prepass_groups")) return &g_sw.prepass_groups;
     if (!std::strcmp(name, "store_policy")) return &g_sw.store_policy;
     return nullptr;
 }
@@ -269,11 +271,11 @@ hipError_t launch_bf16_dma(const ScanLaunch &a, const LaLambdas &lams, hipStream
               : launch_bf16_dma_variant<REV, false, 0>(a, lams, s);
 }
 
-template <int NS>
+template <int G>
 hipError_t launch_prepass_bf16_dma(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
-    using Cfg = DmaPrepassCfg<NS>;
-    auto kern = la_prepass_bf16_dma<NS>;
+    using Cfg = DmaPrepassCfg<G>;
+    auto kern = la_prepass_bf16_dma<G>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
@@ -337,7 +339,11 @@ hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
             if (d == 64) return launch_prepass_bf16<64, false>(a, lams, s);
             if (g_sw.staged_scan.load(std::memory_order_relaxed) || g_sw.staged_prepass.load(std::memory_order_relaxed))
                 return launch_prepass_bf16<128, false>(a, lams, s);
-            return launch_prepass_bf16_dma<5>(a, lams, s);
+            switch (g_sw.prepass_groups.load(std::memory_order_relaxed)) {
+            case 1: return launch_prepass_bf16_dma<1>(a, lams, s);
+            case 2: return launch_prepass_bf16_dma<2>(a, lams, s);
+            default: return launch_prepass_bf16_dma<4>(a, lams, s);
+            }
         }
         if (act) return d == 64 ? launch_bf16<64, REV, true>(a, lams, s) : launch_bf16<128, REV, true>(a, lams, s);
         if (d == 64) return launch_bf16<64, REV, false>(a, lams, s);

@@ -15,11 +15,15 @@
  *                    decay weight is below its cut-off
  *   "f32_plain"      != 0: fp32 at d = 128 runs the plain FMA kernel instead of the
  *                    matrix-core one
- *   "ablate"         1..3: measurement-only variants of the direct-to-LDS block scan that
+ *   "ablate"         1..4: measurement-only variants of the direct-to-LDS block scan that
  *                    leave work out (1: no result stores, 2: loads and barriers only,
- *                    3: arithmetic only); their results are wrong by design
+ *                    3: arithmetic only, 4: loads, barriers and stores without arithmetic);
+ *                    their results are wrong by design
  *   "staged_prepass" != 0: bf16 at d = 128 runs the register-staged segment-state pre-pass
  *                    instead of the direct-to-LDS one
+ *   "prepass_groups" 1, 2: the direct-to-LDS pre-pass runs with that many groups of four waves per
+ *                    workgroup instead of four (each group takes every G-th block of the segment;
+ *                    the sums differ in rounding order between group counts)
  *   "no_trio"        != 0: la_bwd runs its direct-to-LDS block scans as a dQ launch followed by a
  *                    paired dK / dV launch instead of one launch of three roles
  *   "wide_slices"    != 0: la_fwd_wide always runs accumulated scans over d_v-wide slices, also where

@@ -456,32 +456,47 @@ __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLa
 // The local end state of every segment (see la_kernels_prepass.h for what it is and how the
 // launch is laid out: roles, head order, decay cut-off), computed as the state update of the
 // block scan alone: per 32-row block the Bm and C tiles arrive by direct loads (2 x 8 KB per
-// stage, five stages: four blocks of prefetch; two or eight blocks change its time by 6 %
-// either way), Bm^T and this wave's C fragments come from the
-// transposing reads, and the decay is folded into the weights put on the C fragments (row r
-// of block k is weighted by its full distance to the segment's far end), so the accumulator
-// is never rescaled.  One barrier per block, no stores until the state is written out.
-template <int NS_>
+// stage), Bm^T and this wave's C fragments come from the transposing reads, and the decay is
+// folded into the weights put on the C fragments (row r of block k is weighted by its full
+// distance to the segment's far end), so the accumulator is never rescaled and partial sums
+// over any subset of the blocks simply add.
+//
+// That last property is what the workgroup layout uses.  A segment's blocks form one
+// dependent chain (wait for the block, barrier, issue the next load, 20 LDS reads, 8 MFMAs:
+// about 0.45 us), and a slowly decaying head must read all 64 blocks of a 2048-token segment
+// while the quickly decaying heads are long done: measured, such a chain set the kernel's
+// time (50 us where the bytes need 30), whatever the prefetch depth (2, 4 or 8 blocks ahead:
+// +-6 %).  So a workgroup is G = 4 groups of four waves; group q takes blocks q, q + 4, ...
+// with its own two LDS stages and its own accumulators, and at the end the groups' partial
+// states are added through LDS in a fixed order (group 0 + 1 + 2 + 3: deterministic).  The
+// chain is a quarter as long, four of them overlap on one compute unit, and neither the
+// workspace nor any other kernel knows about it.  Measured at 16 heads x 64K tokens (32
+// segments a head): la_fwd 0.283 -> 0.266 ms and la_bwd, with its two pre-passes, 0.623 ->
+// 0.600 ms against one group; two groups give the forward gain but only half the backward one.
+template <int G_>
 struct DmaPrepassCfg {
-    static constexpr int D = 128, BK = 32, NS = NS_, NT = 256;
+    static constexpr int D = 128, BK = 32, NS = 2, G = G_, NT = 256 * G_;
     static constexpr int TILE_BYTES = BK * D * 2;
     static constexpr int STAGE_BYTES = 2 * TILE_BYTES;       // Bm, C
-    static constexpr size_t lds_bytes = (size_t)NS * STAGE_BYTES;   // 81920
+    static constexpr size_t raw_bytes = (size_t)G * NS * STAGE_BYTES;
+    // the partial states are exchanged through a [64][256] fp32 area laid over the stages
+    static constexpr size_t lds_bytes = raw_bytes > 65536 ? raw_bytes : 65536;
 };
 
-template <int NS_>
-__global__ __launch_bounds__(256, 2) void la_prepass_bf16_dma(ScanLaunch launch, LaLambdas lams)
+template <int G_>
+__global__ __launch_bounds__(256 * G_, 1) void la_prepass_bf16_dma(ScanLaunch launch, LaLambdas lams)
 {
-    using Cfg = DmaPrepassCfg<NS_>;
-    constexpr int D = Cfg::D, BK = Cfg::BK, NS = Cfg::NS, PF = NS - 1;
+    using Cfg = DmaPrepassCfg<G_>;
+    constexpr int D = Cfg::D, BK = Cfg::BK, NS = Cfg::NS, G = Cfg::G;
     constexpr int KS_B = BK / 16, MT_D = D / 32;
-    constexpr int LOADS = 4;                   // direct loads per wave and block (2 tiles x 2 slots)
 
     extern __shared__ __align__(16) unsigned char smem_dma[];
 
     const int tid = threadIdx.x;
     const int l = tid & 63, l32 = l & 31, g = l >> 5;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int w = wv & 3;                                    // value-feature slice of this wave
+    const int gq = wv >> 2;                                  // group: blocks gq, gq + G, ...
 
     const int role = launch.nroles == 2 ? (int)(blockIdx.x / launch.items) : 0;
     const int item = launch.nroles == 2 ? (int)(blockIdx.x % launch.items) : (int)blockIdx.x;
@@ -504,6 +519,7 @@ __global__ __launch_bounds__(256, 2) void la_prepass_bf16_dma(ScanLaunch launch,
         const float reach = a.skip_bits / -lg;
         if (reach < (float)(nblk * BK)) ib0 = max(0, nblk - ((int)(reach / BK) + 2));
     }
+    const int rounds = (nblk - ib0 + G - 1) / G;             // iterations, the same for every group
 
     const size_t base = (size_t)scan * a.n * D;
     const uint16_t *gB = (const uint16_t *)a.Bm + base;
@@ -526,6 +542,7 @@ __global__ __launch_bounds__(256, 2) void la_prepass_bf16_dma(ScanLaunch launch,
         dma_col[j] = 8 * ((l & 15) ^ dma_sw(dma_row[j]));
     }
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(la_lds_void *)smem_dma);
+    const int group_off = gq * NS * Cfg::STAGE_BYTES;
 
     f32x16_t st[MT_D];
 #pragma unroll
@@ -539,24 +556,23 @@ __global__ __launch_bounds__(256, 2) void la_prepass_bf16_dma(ScanLaunch launch,
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const size_t off = (size_t)min(t0 + dma_row[j], seg_hi - 1) * D + dma_col[j];
-            const uint32_t dst = lds0 + stage * Cfg::STAGE_BYTES + (2 * w + j) * 1024;
+            const uint32_t dst = lds0 + group_off + stage * Cfg::STAGE_BYTES + (2 * w + j) * 1024;
             dma_load16<true>(gB + off, dst);
             dma_load16<true>(gC + off, dst + Cfg::TILE_BYTES);
         }
     };
 
-#pragma unroll
-    for (int i = 0; i < PF; ++i)
-        if (ib0 + i < nblk) issue(ib0 + i, i);
+    if (ib0 + gq < nblk) issue(ib0 + gq, 0);
 
-    int stage = 0;
-    for (int ib = ib0; ib < nblk; ++ib) {
-        const int blk = blk_of(ib);
+    for (int it = 0; it < rounds; ++it) {
+        const int ib = ib0 + gq + it * G;
+        const bool live = ib < nblk;
+        const int stage = it & 1;
+        unsigned char *sb = smem_dma + group_off + stage * Cfg::STAGE_BYTES;
+        const int blk = blk_of(live ? ib : ib0);
         const int t0 = seg_lo + blk * BK;
-        unsigned char *sb = smem_dma + stage * Cfg::STAGE_BYTES;
-        // younger than this block's loads: those of the next min(PF - 1, blocks left) blocks
-        la_wait_vm_le<(PF - 1) * LOADS>(LOADS * min(PF - 1, nblk - 1 - ib));
-        if (t0 + BK > seg_hi) {                 // partial block: zero padding (exact)
+        la_wait_vm<0>();                        // this group's only outstanding loads are this block's
+        if (live && t0 + BK > seg_hi) {         // partial block: zero padding (exact)
             const U4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int j = 0; j < 2; ++j)
@@ -566,15 +582,13 @@ __global__ __launch_bounds__(256, 2) void la_prepass_bf16_dma(ScanLaunch launch,
                     *(U4 *)(dst + Cfg::TILE_BYTES) = z;
                 }
         }
-        LA_LDS_BARRIER();                       // landed for every wave; the previous block's stage is free
-        if (ib + PF < nblk) issue(ib + PF, stage >= 1 ? stage - 1 : NS - 1);
+        LA_LDS_BARRIER();                       // landed for every wave; the other stage is free
+        if (ib + G < nblk) issue(ib + G, stage ^ 1);
+        if (!live) continue;
 
         const unsigned char *sB = sb, *sC = sb + Cfg::TILE_BYTES;
         // distance of this block to the segment's far end, folded into the weights
         const float mu = rev ? pw(blk * BK) : pw((nblk - 1 - blk) * BK);
-        // All twenty transposing reads of the block are issued before anything waits for them:
-        // a slowly decaying head's workgroup is often alone on its compute unit, and with one
-        // wave per SIMD every exposed LDS latency is paid in full.
         U2 rc[KS_B][2], rb[MT_D][KS_B][2];
 #pragma unroll
         for (int ks = 0; ks < KS_B; ++ks) {
@@ -608,7 +622,30 @@ __global__ __launch_bounds__(256, 2) void la_prepass_bf16_dma(ScanLaunch launch,
                 const U4 bt = {rb[mt][ks][0][0], rb[mt][ks][0][1], rb[mt][ks][1][0], rb[mt][ks][1][1]};
                 st[mt] = mfma32(bt, cw[ks], st[mt]);
             }
-        stage = stage + 1 < NS ? stage + 1 : 0;
+    }
+
+    // ---- the groups' partial states, added in a fixed order through LDS ------------------
+    if (G > 1) {
+        float *sX = reinterpret_cast<float *>(smem_dma);     // [64][256]: entry (mt, v) of thread (w, l)
+        LA_LDS_BARRIER();                       // every group is done with its stages
+#pragma unroll 1
+        for (int r = 1; r < G; ++r) {
+            if (gq == r) {
+#pragma unroll
+                for (int mt = 0; mt < MT_D; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) sX[(16 * mt + v) * 256 + 64 * w + l] = st[mt][v];
+            }
+            LA_LDS_BARRIER();
+            if (gq == 0) {
+#pragma unroll
+                for (int mt = 0; mt < MT_D; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) st[mt][v] += sX[(16 * mt + v) * 256 + 64 * w + l];
+            }
+            LA_LDS_BARRIER();
+        }
+        if (gq != 0) return;
     }
 
 #pragma unroll

@@ -455,3 +455,27 @@ def test_direct_to_lds_and_register_staged_block_scans_agree():
             split = _run_gpu(w, xs, lseg=lseg)
         for a, b in zip(direct, split):
             assert np.array_equal(a, b)
+
+
+def test_prepass_wave_group_counts_agree():
+    """The direct-to-LDS segment-state pre-pass splits a segment's blocks over G groups of four
+    waves and adds the groups' partial states at the end (G = 4; 1 and 2 behind the
+    "prepass_groups" switch).  Every count gives the oracle's result within the tolerance, with a
+    ragged last block, a ragged last segment, segments shorter than G blocks, and a quickly
+    decaying head whose cut-off leaves fewer blocks than groups; counts differ only by rounding
+    order."""
+    lam = [1.0, 0.9995, 0.97, 0.5]
+    for n, lseg in ((1337, 256), (1000, 64), (4099, 2048)):
+        w = synth.custom(2, 4, n, 128, lam, seed=99 + n, dtype="bf16")
+        xs = synth.draw(w)
+        q, k, v, g = _ref_inputs(xs, "bf16")
+        ref = (oracle.c_recurrence_fwd(q, k, v, lam),) + oracle.c_recurrence_bwd(q, k, v, lam, g)
+        runs = {}
+        for groups in (4, 2, 1):
+            _say("n=%d lseg=%d groups=%d" % (n, lseg, groups))
+            with binding.debug(prepass_groups=0 if groups == 4 else groups):
+                runs[groups] = _run_gpu(w, xs, lseg=lseg)
+            _compare(w, runs[groups], ref, TOL["bf16"], "n=%d lseg=%d groups=%d" % (n, lseg, groups))
+        for groups in (2, 1):
+            for a, b in zip(runs[4], runs[groups]):
+                assert oracle.rel_max_err(a, b) <= 8e-3          # a bf16 rounding step of the largest element
