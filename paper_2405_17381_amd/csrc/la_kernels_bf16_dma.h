@@ -589,39 +589,50 @@ __global__ __launch_bounds__(256 * G_, 1) void la_prepass_bf16_dma(ScanLaunch la
         const unsigned char *sB = sb, *sC = sb + Cfg::TILE_BYTES;
         // distance of this block to the segment's far end, folded into the weights
         const float mu = rev ? pw(blk * BK) : pw((nblk - 1 - blk) * BK);
-        U2 rc[KS_B][2], rb[MT_D][KS_B][2];
-#pragma unroll
-        for (int ks = 0; ks < KS_B; ++ks) {
-            const unsigned char *p = sC + tr_base + 16 * ks * 256;
-            rc[ks][0] = lds_read_tr(p + ((((4 * w) ^ tr_sw)) << 4));
-            rc[ks][1] = lds_read_tr(p + 8 * 256 + ((((4 * w) ^ tr_sw ^ 2)) << 4));
-        }
-#pragma unroll
-        for (int mt = 0; mt < MT_D; ++mt)
-#pragma unroll
-            for (int ks = 0; ks < KS_B; ++ks) {
-                const unsigned char *p = sB + tr_base + 16 * ks * 256;
-                rb[mt][ks][0] = lds_read_tr(p + ((((4 * mt) ^ tr_sw)) << 4));
-                rb[mt][ks][1] = lds_read_tr(p + 8 * 256 + ((((4 * mt) ^ tr_sw ^ 2)) << 4));
-            }
-        LA_BATCH_FENCE();
+        // the LDS reads go out in batches (one of 20 reads; at four groups, where a wave has a
+        // quarter of the registers, two of 12 and 8), each followed by its MFMAs: independent
+        // accumulator chains, interleaved
+        constexpr int MB = G == 4 ? 2 : MT_D;
+        U2 rc[KS_B][2];
         U4 cw[KS_B];
 #pragma unroll
-        for (int ks = 0; ks < KS_B; ++ks) {
-            const U4 cf = {rc[ks][0][0], rc[ks][0][1], rc[ks][1][0], rc[ks][1][1]};
+        for (int m0 = 0; m0 < MT_D; m0 += MB) {
+            U2 rb[MB][KS_B][2];
+            if (m0 == 0) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                cw[ks][e] = pack2_bf16(bf16_lo(cf[e]) * (wt[8 * ks + 2 * e] * mu),
-                                       bf16_hi(cf[e]) * (wt[8 * ks + 2 * e + 1] * mu));
-        }
-        // four independent accumulator chains, interleaved
-#pragma unroll
-        for (int ks = 0; ks < KS_B; ++ks)
-#pragma unroll
-            for (int mt = 0; mt < MT_D; ++mt) {
-                const U4 bt = {rb[mt][ks][0][0], rb[mt][ks][0][1], rb[mt][ks][1][0], rb[mt][ks][1][1]};
-                st[mt] = mfma32(bt, cw[ks], st[mt]);
+                for (int ks = 0; ks < KS_B; ++ks) {
+                    const unsigned char *p = sC + tr_base + 16 * ks * 256;
+                    rc[ks][0] = lds_read_tr(p + ((((4 * w) ^ tr_sw)) << 4));
+                    rc[ks][1] = lds_read_tr(p + 8 * 256 + ((((4 * w) ^ tr_sw ^ 2)) << 4));
+                }
             }
+#pragma unroll
+            for (int m = 0; m < MB; ++m)
+#pragma unroll
+                for (int ks = 0; ks < KS_B; ++ks) {
+                    const unsigned char *p = sB + tr_base + 16 * ks * 256;
+                    rb[m][ks][0] = lds_read_tr(p + ((((4 * (m0 + m)) ^ tr_sw)) << 4));
+                    rb[m][ks][1] = lds_read_tr(p + 8 * 256 + ((((4 * (m0 + m)) ^ tr_sw ^ 2)) << 4));
+                }
+            LA_BATCH_FENCE();
+            if (m0 == 0) {
+#pragma unroll
+                for (int ks = 0; ks < KS_B; ++ks) {
+                    const U4 cf = {rc[ks][0][0], rc[ks][0][1], rc[ks][1][0], rc[ks][1][1]};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        cw[ks][e] = pack2_bf16(bf16_lo(cf[e]) * (wt[8 * ks + 2 * e] * mu),
+                                               bf16_hi(cf[e]) * (wt[8 * ks + 2 * e + 1] * mu));
+                }
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS_B; ++ks)
+#pragma unroll
+                for (int m = 0; m < MB; ++m) {
+                    const U4 bt = {rb[m][ks][0][0], rb[m][ks][0][1], rb[m][ks][1][0], rb[m][ks][1][1]};
+                    st[m0 + m] = mfma32(bt, cw[ks], st[m0 + m]);
+                }
+        }
     }
 
     // ---- the groups' partial states, added in a fixed order through LDS ------------------
