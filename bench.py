@@ -94,14 +94,29 @@ def ablation(binding, torch, views, lam, ws):
              ("la_bwd as a dQ launch + a paired dK/dV launch (not one launch of three roles)", {"no_trio": 1}),
              ("register-staged scan and pre-pass (64-row blocks)", {"staged_scan": 1}),
              ("register-staged pre-pass only", {"staged_prepass": 1}),
+             ("direct-to-LDS pre-pass with one group of four waves per workgroup (not four)", {"prepass_groups": 1}),
              ("ordinary result stores", {"store_policy": 2}),
              ("ablate 1: no result stores", {"ablate": 1}),
              ("ablate 2: loads, waits and barriers only", {"ablate": 2}),
              ("ablate 3: arithmetic only (no loads, no stores)", {"ablate": 3}),
              ("ablate 4: loads, barriers and result stores, no arithmetic", {"ablate": 4})]
     out = {"protocol": "median ms of 20 calls, two interleaved rounds; fwd = la_fwd, bwd = la_bwd, "
-                       "fwd_bwd = the two back to back; H=16, d=128, bf16, 65536 tokens", "cases": []}
+                       "fwd_bwd = the two back to back, sweep_step_ms = one fwd+bwd at each of the six "
+                       "sweep points in turn (the benchmark's step); H=16, d=128, bf16, 65536 tokens",
+           "cases": []}
     fns = {}
+    step_fns = []
+    for B, n in ((32, 2048), (16, 4096), (8, 8192), (4, 16384), (2, 32768), (1, 65536)):
+        t = views(B, n)
+        step_fns.append(lambda t=t: (
+            binding.la_fwd(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=ws),
+            binding.la_bwd(t["Q"], t["K"], t["V"], lam, t["dO"], dQ=t["dQ"], dK=t["dK"], dV=t["dV"],
+                           workspace=ws)))
+
+    def sweep_step():
+        for fn in step_fns:
+            fn()
+
     for B, n in ((32, 2048), (1, 65536)):
         t = views(B, n)
         f = lambda t=t: binding.la_fwd(t["Q"], t["K"], t["V"], lam, O=t["O"], workspace=ws)
@@ -116,6 +131,7 @@ def ablation(binding, torch, views, lam, ws):
                 for (B, n), (f, b) in fns.items():
                     row["B%d_n%d" % (B, n)] = {"fwd_ms": med(f), "bwd_ms": med(b),
                                                "fwd_bwd_ms": med(lambda: (f(), b()))}
+                row["sweep_step_ms"] = med(sweep_step)
             out["cases"].append(row)
     return out
 

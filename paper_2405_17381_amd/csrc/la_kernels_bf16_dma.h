@@ -462,17 +462,19 @@ __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLa
 // over any subset of the blocks simply add.
 //
 // That last property is what the workgroup layout uses.  A segment's blocks form one
-// dependent chain (wait for the block, barrier, issue the next load, 20 LDS reads, 8 MFMAs:
-// about 0.45 us), and a slowly decaying head must read all 64 blocks of a 2048-token segment
-// while the quickly decaying heads are long done: measured, such a chain set the kernel's
-// time (50 us where the bytes need 30), whatever the prefetch depth (2, 4 or 8 blocks ahead:
-// +-6 %).  So a workgroup is G = 4 groups of four waves; group q takes blocks q, q + 4, ...
-// with its own two LDS stages and its own accumulators, and at the end the groups' partial
-// states are added through LDS in a fixed order (group 0 + 1 + 2 + 3: deterministic).  The
-// chain is a quarter as long, four of them overlap on one compute unit, and neither the
-// workspace nor any other kernel knows about it.  Measured at 16 heads x 64K tokens (32
-// segments a head): la_fwd 0.283 -> 0.266 ms and la_bwd, with its two pre-passes, 0.623 ->
-// 0.600 ms against one group; two groups give the forward gain but only half the backward one.
+// dependent chain (wait for the block, barrier, issue the next load, 20 LDS reads, 8 MFMAs),
+// and a slowly decaying head must read all 64 blocks of a 2048-token segment while the quickly
+// decaying heads are long done.  A workgroup is therefore G = 4 groups of four waves; group q
+// takes blocks q, q + 4, ... with its own two LDS stages and its own accumulators, and at the
+// end the groups' partial states are added through LDS in a fixed order (group 0 + 1 + 2 + 3:
+// deterministic).  The chain is a quarter as long and four of them overlap on one compute
+// unit; neither the workspace nor any other kernel knows about it.  Measured at 16 heads x
+// 64K tokens (32 segments a head), la_fwd / la_bwd in ms: one group with two stages 0.285 /
+// 0.612, two groups 0.267 / 0.600, four groups 0.261 / 0.604; one group with five stages
+// (four blocks of prefetch, the earlier layout) 0.266 / 0.62.  All but the first sit at about
+// 45 us per launch of 512 workgroups, i.e. the kernel's 224 MB at 5 TB/s: the pre-pass is
+// bound by its bytes and by the ramp of a short launch, not by the chain, once either the
+// prefetch is deep enough or the chain is split.
 template <int G_>
 struct DmaPrepassCfg {
     static constexpr int D = 128, BK = 32, NS = 2, G = G_, NT = 256 * G_;
