@@ -314,7 +314,7 @@ def main():
     roofline["measured_stream_GBps"] = round(stream_gbs, 1)
     roofline["frac_of_measured_stream"] = round(achieved / stream_gbs, 4)
 
-    decode = gate_norm = swish_fused = lrpe = fp32_path = saved_states = other_configs = None
+    decode = gate_norm = swish_fused = lrpe = fp32_path = saved_states = other_configs = graph_replay = None
     mfma_measured = None
     if not args.sweep_only:
         # ---- decode step (next row after the training path): B=8, H=32, d=128, bf16 ----------
@@ -434,6 +434,21 @@ def main():
                         "plain_fwd_bwd_ms": sweep[-1]["fwd_bwd_ms"] if sweep[-1]["n"] == TOKENS else None,
                         "note": "not the headline: la_bwd takes no saved context by contract"}
 
+        # ---- the sweep step captured once into a HIP graph and replayed (same calls, same kernels; only
+        # the launches are issued by the graph instead of one by one from the host) -------------------------
+        if not args.calib_copy and not args.point:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            gr = _time(graph.replay, it=20, key="graph")
+            ea = _time(step, it=20, key="eager")
+            graph_replay = {"workload": "the headline step (fwd+bwd at the six sweep points) as one replay of a "
+                                        "captured HIP graph",
+                            "ms_per_step": round(gr, 4), "ms_per_step_min": leg_min["graph"],
+                            "tokens_per_s": round(tokens_per_step / (gr * 1e-3), 1),
+                            "eager_ms_per_step": round(ea, 4), "eager_ms_per_step_min": leg_min["eager"],
+                            "note": "not the headline: the headline times the C-ABI calls issued one by one"}
+
         # ---- the other bf16 configurations (parity cases; timed here so that their rates come from the
         # same run and protocol): C2 (TNL-400M-shaped layer, d = 64), C4 (TNL-7B-shaped layer), C5 (one
         # 131072-token sequence, half of the heads without decay) ------------------------------------------
@@ -552,6 +567,7 @@ def main():
         "lrpe_d": lrpe,
         "fp32_path": fp32_path,
         "saved_states": saved_states,
+        "graph_replay": graph_replay,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()

@@ -41,6 +41,11 @@
  *   - Calls are thread-safe (no global mutable state apart from the optional
  *     profiling hooks below) and results are bitwise reproducible from run to
  *     run: no atomics are used in any reduction.  The environment is never read.
+ *   - Every entry point that takes a stream only launches kernels on it (no memory-set or
+ *     copy nodes, no events unless the profiling hooks are on), so calls can be recorded
+ *     into a HIP graph by stream capture and replayed.  The first launch of each kernel in
+ *     a process sets a function attribute (its dynamic LDS size): make one ordinary call
+ *     of the same entry point and shape before capturing.
  *   - The launch planner is written for MI355X: it assumes 256 compute units when it
  *     decides whether, and how finely, a sequence is cut into segments.  On a part
  *     with another count the results are the same, only the occupancy differs.
