@@ -298,8 +298,8 @@ int la_lrpe_rotate_bwd(const void *X, const float *theta /* device, [H, d] */, c
  * attention runs per head.  Q, K, V share one layout; O (forward), dO, and dQ, dK, dV
  * (backward) have their own.  Strides are in elements, multiples of 8, row_stride
  * >= d (else LA_ERR_ALIGN / LA_ERR_SHAPE); outputs must not overlap anything.
- * Everything else as la_fwd / la_bwd; same arithmetic, and the same results up to rounding
- * order (for bf16 at d = 128 la_fwd / la_bwd run a kernel with shorter blocks).
+ * Everything else as la_fwd / la_bwd: the same kernels with explicit strides, and the same
+ * results bit for bit as la_fwd / la_bwd on contiguous copies of the tensors.
  */
 typedef struct la_layout {
     long long batch_stride, head_stride, row_stride;

@@ -222,10 +222,11 @@ hipError_t launch_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s
 }
 
 // The backward pass's three block scans in one launch (see the kernel).
+template <bool STRIDED>
 hipError_t launch_bf16_dma_trio(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
     using Cfg = DmaCfg<3>;
-    auto kern = la_scan_bf16_dma<false, true, 0, 3, true>;
+    auto kern = la_scan_bf16_dma<false, true, 0, 3, true, STRIDED>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
@@ -235,11 +236,11 @@ hipError_t launch_bf16_dma_trio(const ScanLaunch &a, const LaLambdas &lams, hipS
     return hipGetLastError();
 }
 
-template <bool REV, bool NT_STORE, int ABL, int NS = 3>
+template <bool REV, bool NT_STORE, int ABL, int NS = 3, bool STRIDED = false>
 hipError_t launch_bf16_dma_variant(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
     using Cfg = DmaCfg<NS>;
-    auto kern = la_scan_bf16_dma<REV, NT_STORE, ABL, NS>;
+    auto kern = la_scan_bf16_dma<REV, NT_STORE, ABL, NS, false, STRIDED>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
@@ -255,10 +256,12 @@ hipError_t launch_bf16_dma_variant(const ScanLaunch &a, const LaLambdas &lams, h
 // faster with ordinary stores, but only because L2 then hands part of its write-back to
 // whatever runs next: over a forward + backward sequence non-temporal stores in all three
 // launches win by 6 % ("store_policy" switch = 2 selects ordinary stores, for measurements).
-template <bool REV>
+template <bool REV, bool STRIDED = false>
 hipError_t launch_bf16_dma(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
     const bool nt = g_sw.store_policy.load(std::memory_order_relaxed) != 2;
+    // operands with their own layouts (strided entry points, slices of wider rows): one variant
+    if (STRIDED) return launch_bf16_dma_variant<REV, true, 0, 3, true>(a, lams, s);
     switch (g_sw.ablate.load(std::memory_order_relaxed)) {
     case 1: return launch_bf16_dma_variant<REV, true, 1>(a, lams, s);
     case 2: return launch_bf16_dma_variant<REV, true, 2>(a, lams, s);
@@ -271,11 +274,11 @@ hipError_t launch_bf16_dma(const ScanLaunch &a, const LaLambdas &lams, hipStream
               : launch_bf16_dma_variant<REV, false, 0>(a, lams, s);
 }
 
-template <int G>
+template <int G, bool STRIDED = false>
 hipError_t launch_prepass_bf16_dma(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
     using Cfg = DmaPrepassCfg<G>;
-    auto kern = la_prepass_bf16_dma<G>;
+    auto kern = la_prepass_bf16_dma<G, STRIDED>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
@@ -333,7 +336,17 @@ hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
 {
     if (dt == LA_BF16) {
         // the plain path runs kernels without any activation code in them
-        const bool act = (a.r[0].act | a.r[a.nroles - 1].act) != 0;
+        const int acts = a.r[0].act | a.r[a.nroles - 1].act;
+        // operands with their own layouts and nothing else: the direct-to-LDS kernels, strided
+        const bool staged128 = g_sw.staged_scan.load(std::memory_order_relaxed) != 0;
+        if (acts == LA_ACT_EXT && d == 128 && !staged128) {
+            if (STATE_ONLY) {
+                if (g_sw.staged_prepass.load(std::memory_order_relaxed)) return launch_prepass_bf16<128, true>(a, lams, s);
+                return launch_prepass_bf16_dma<4, true>(a, lams, s);
+            }
+            return launch_bf16_dma<REV, true>(a, lams, s);
+        }
+        const bool act = acts != 0;
         if (STATE_ONLY) {
             if (act) return d == 64 ? launch_prepass_bf16<64, true>(a, lams, s) : launch_prepass_bf16<128, true>(a, lams, s);
             if (d == 64) return launch_prepass_bf16<64, false>(a, lams, s);
@@ -552,13 +565,16 @@ int run_backward(const void *Q, const void *K, const void *V, const void *dO, vo
         }
         if (rc != LA_OK) return rc;
     }
+    const int acts = pre[0].act | pre[1].act | av.act;
+    const bool all_ext = pre[0].act == LA_ACT_EXT && pre[1].act == LA_ACT_EXT && av.act == LA_ACT_EXT;
     if (!g_sw.no_trio.load(std::memory_order_relaxed) && dt == LA_BF16 && d == 128 &&
-        !(pre[0].act | pre[1].act | av.act) && !g_sw.staged_scan.load(std::memory_order_relaxed) &&
+        (acts == 0 || all_ext) && !g_sw.staged_scan.load(std::memory_order_relaxed) &&
         !g_sw.no_pair.load(std::memory_order_relaxed) && !g_sw.ablate.load(std::memory_order_relaxed)) {
         ScanLaunch l;
         l.r[0] = pre[0]; l.r[1] = pre[1]; l.r[2] = av; l.nroles = 3; l.items = (int)(scans * p.S);
         ScopedTimer t(s);
-        return launch_bf16_dma_trio(l, lams, s) == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
+        const hipError_t e = all_ext ? launch_bf16_dma_trio<true>(l, lams, s) : launch_bf16_dma_trio<false>(l, lams, s);
+        return e == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
     }
     int rc = run_block_scan<false>(pre[0], lams, scans, d, dt, s);
     if (rc != LA_OK) return rc;

@@ -122,14 +122,16 @@ def test_lrpe_d_through_the_wide_entry_point():
 
 
 def test_dk_equal_dv_is_the_plain_attention_bit_for_bit():
+    """One slice of the full width: the wide entry points run the plain attention's kernels with an
+    explicit row stride, in either kernel family of bf16 at d = 128."""
     lam = [0.99, 0.9]
     xs = _draw(2, 2, 500, 128, 128, "bf16", seed=62)
-    wide = _run(xs, lam, None)
     Q, K, V, dO = [x.cuda() for x in xs]
-    # (the wide entry points run the register-staged block scan: compare within that family)
-    with binding.debug(staged_scan=1):
-        O = binding.la_fwd(Q, K, V, lam)
-        dQ, dK, dV = binding.la_bwd(Q, K, V, lam, dO)
-        torch.cuda.synchronize()
-    for a, b in zip(wide, (O, dQ, dK, dV)):
-        assert np.array_equal(a, b.double().cpu().numpy())
+    for staged in (0, 1):
+        with binding.debug(staged_scan=staged):
+            wide = _run(xs, lam, None)
+            O = binding.la_fwd(Q, K, V, lam)
+            dQ, dK, dV = binding.la_bwd(Q, K, V, lam, dO)
+            torch.cuda.synchronize()
+        for a, b in zip(wide, (O, dQ, dK, dV)):
+            assert np.array_equal(a, b.double().cpu().numpy()), "staged_scan=%d" % staged
