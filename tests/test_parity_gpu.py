@@ -333,56 +333,6 @@ def test_planner_segments_a_small_batch_by_itself(dtype, d, n):
     _full_case(w)
 
 
-def test_hip_graph_capture_and_replay():
-    """The calls only enqueue kernels (decay rates travel in the kernel arguments,
-    nothing is allocated, copied or memset), so a forward+backward can be captured
-    into a HIP graph; every replay must reproduce the eager result bit for bit."""
-    lam = [1.0, 0.999, 0.95, 0.7]
-    w = synth.custom(2, 4, 1500, 128, lam, seed=11, dtype="bf16")
-    binding.debug_set("lseg", 512)                 # pre-pass, segment scan and block scans
-    try:
-        Q, K, V, dO = _to_dev(synth.draw(w), "bf16")
-        need = binding.la_workspace_bytes(w.B, w.H, w.n, w.d, binding.LA_BF16, True)
-        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
-        outs = [torch.empty_like(Q) for _ in range(4)]
-
-        def run():
-            binding.la_fwd(Q, K, V, lam, O=outs[0], workspace=ws)
-            binding.la_bwd(Q, K, V, lam, dO, dQ=outs[1], dK=outs[2], dV=outs[3], workspace=ws)
-
-        run()                                      # eager warm-up (sets kernel attributes)
-        torch.cuda.synchronize()
-        eager = [o.clone() for o in outs]
-        graph = torch.cuda.CUDAGraph()
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph, stream=side):
-                run()
-        torch.cuda.synchronize()
-        for rep in range(3):
-            for o in outs:
-                o.fill_(float("nan"))              # eager work between the replays
-            torch.cuda.synchronize()
-            graph.replay()
-            torch.cuda.synchronize()
-            for o, e in zip(outs, eager):
-                assert torch.equal(o, e), rep
-        # new inputs in the captured buffers
-        Q2, K2, V2, dO2 = _to_dev(synth.draw(synth.custom(2, 4, 1500, 128, lam, seed=12, dtype="bf16")), "bf16")
-        for dst, src in ((Q, Q2), (K, K2), (V, V2), (dO, dO2)):
-            dst.copy_(src)
-        graph.replay()
-        torch.cuda.synchronize()
-        replayed = [o.clone() for o in outs]
-        run()
-        torch.cuda.synchronize()
-        for o, r in zip(outs, replayed):
-            assert torch.equal(o, r)
-    finally:
-        binding.debug_set("lseg", 0)
-
-
 @pytest.mark.parametrize("dtype,d,n,lseg", [("bf16", 128, 5000, None), ("bf16", 64, 1500, 256), ("f32", 128, 700, 128),
                                              ("f32", 64, 900, 256), ("bf16", 128, 300, None)])
 def test_backward_reusing_the_forward_states(dtype, d, n, lseg):
@@ -479,3 +429,31 @@ def test_prepass_wave_group_counts_agree():
         for groups in (2, 1):
             for a, b in zip(runs[4], runs[groups]):
                 assert oracle.rel_max_err(a, b) <= 8e-3          # a bf16 rounding step of the largest element
+
+
+def _random_case(i):
+    """Case i of a fixed pseudo-random list: shapes, decay rates and segment lengths nobody chose by hand."""
+    rng = np.random.default_rng(9000 + i)
+    dtype = ("bf16", "bf16", "f32")[i % 3]
+    d = (128, 64)[(i // 3) % 2]
+    B = int(rng.integers(1, 4))
+    H = int(rng.integers(1, 7))
+    n = int(rng.integers(1, 1600 if dtype == "bf16" else 700))
+    kind = rng.random(H)
+    lam = [1.0 if k < 0.15 else float(1.0 - 10.0 ** rng.uniform(-4.0, -0.3)) for k in kind]
+    lseg = (None, 64, 128, 192, 512)[int(rng.integers(0, 5))]
+    return dtype, d, B, H, n, lam, lseg
+
+
+@pytest.mark.parametrize("i", range(24))
+def test_pseudo_random_shapes(i):
+    """24 seeded draws of (dtype, d, B, H, n, decay rates in (0.5, 1], forced segment length):
+    O and all gradients against the oracle's recurrence."""
+    dtype, d, B, H, n, lam, lseg = _random_case(i)
+    _say("case %d: %s d=%d B=%d H=%d n=%d lseg=%s lambda=%s" % (i, dtype, d, B, H, n, lseg, ["%.5f" % x for x in lam]))
+    w = synth.custom(B, H, n, d, lam, seed=9100 + i, dtype=dtype)
+    xs = synth.draw(w)
+    q, k, v, g = _ref_inputs(xs, dtype)
+    ref = (oracle.c_recurrence_fwd(q, k, v, w.lambdas),) + oracle.c_recurrence_bwd(q, k, v, w.lambdas, g)
+    got = _run_gpu(w, xs, lseg=lseg)
+    _compare(w, got, ref, TOL[dtype], "case %d" % i)
