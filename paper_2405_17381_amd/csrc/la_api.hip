@@ -515,7 +515,8 @@ int run_reverse_pair(const ScanArgs &ak, const ScanArgs &av, const LaLambdas &la
 // Backward pass.  dQ = scan(dO, V, K) is the first loop of Alg. 6 (state KV^T); the
 // second loop is the reverse pair above.  With segments, the two pre-passes (forward
 // states of (V, K), reverse states of (dO, Q)) run as one launch into the two halves
-// of the scratch, then the two segment scans, then the block scans.
+// of the scratch, then the two segment scans, then the block scans: for bf16 at d = 128
+// without activations all three as the roles of one launch, else dQ's and the pair's.
 // With `swish`, Q and K are pre-activations: they are activated wherever they are an
 // operand, and dQ, dK are multiplied by phi'(Q), phi'(K) as they are stored.
 int run_backward(const void *Q, const void *K, const void *V, const void *dO, void *dQ, void *dK,
@@ -584,7 +585,7 @@ int run_backward(const void *Q, const void *K, const void *V, const void *dO, vo
 int check_workspace(const Plan &p, int B, int H, int d, void *workspace, size_t workspace_bytes,
                     bool is_bwd)
 {
-    // one workgroup per (scan, segment), two in a paired launch: keep the grid within 2^31
+    // one workgroup per (scan, segment) and role, up to three roles in a launch: keep the grid within 2^31
     if ((long)B * H * p.S > (1L << 29)) return LA_ERR_SHAPE;
     const size_t need = state_bytes(p, B, H, d) * (is_bwd ? 2 : 1);
     if (need == 0) return LA_OK;

@@ -127,9 +127,13 @@ __device__ __forceinline__ U2 lds_read_tr(const unsigned char *p)
 // TRIO: one launch holds the three scans of the backward pass, dQ forward in time and dK, dV
 // reversed, the three workgroups of a (scan, segment) item side by side on one XCD; the direction is
 // then a run-time property of the role and every tile load is cacheable (each tensor is read by two
-// or three of the roles).  Measured against a dQ launch followed by a paired dK / dV launch: 3 to 5 %
-// less time for la_bwd, with slightly MORE bytes fetched (1.05 x): what it saves is the boundary
-// between two launches that each fill and drain the machine, not traffic.
+// or three of the roles).  Measured against a dQ launch followed by a paired dK / dV launch: the
+// kernel time is 3 % less (503 against 197 + 324 us under the profiler), a whole forward + backward
+// step between level and 1.4 % faster depending on the box; what it saves is the boundary between
+// two launches that each fill and drain the machine, and, while the tiles of the resident workgroups
+// fit the Infinity Cache (sequences or segments of up to about 1024 tokens), a part of the reads
+// that the forward and the reversed roles have in common.
+// STRIDED: every operand has its own layout (ScanArgs::lA .. lO) instead of contiguous slabs.
 template <bool REV_, bool NT_STORE, int ABL, int NS_, bool TRIO = false, bool STRIDED = false>
 __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLaunch launch, LaLambdas lams)
 {
