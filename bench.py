@@ -314,7 +314,7 @@ def main():
     roofline["measured_stream_GBps"] = round(stream_gbs, 1)
     roofline["frac_of_measured_stream"] = round(achieved / stream_gbs, 4)
 
-    decode = gate_norm = swish_fused = lrpe = fp32_path = saved_states = other_configs = graph_replay = None
+    decode = gate_norm = swish_fused = lrpe = fp32_path = saved_states = other_configs = graph_replay = token_major = None
     mfma_measured = None
     if not args.sweep_only:
         # ---- decode step (next row after the training path): B=8, H=32, d=128, bf16 ----------
@@ -433,6 +433,23 @@ def main():
                         "tokens_per_s": round(TOKENS / (sv * 1e-3), 1),
                         "plain_fwd_bwd_ms": sweep[-1]["fwd_bwd_ms"] if sweep[-1]["n"] == TOKENS else None,
                         "note": "not the headline: la_bwd takes no saved context by contract"}
+
+        # ---- token-major tensors ([B, n, H, d], what the layer's projections write) through the strided
+        # entry points: the same memory read as permuted views, no transpose --------------------------------
+        token_major = []
+        for sB, sn in ((32, 2048), (8, 8192), (1, TOKENS)):
+            tm = {k: v.view(sB, sn, H, D).permute(0, 2, 1, 3) for k, v in flat.items()}
+            tf = _time(lambda: binding.la_fwd_strided(tm["Q"], tm["K"], tm["V"], lam, O=tm["O"], workspace=ws), key="tmf")
+            tb = _time(lambda: binding.la_bwd_strided(tm["Q"], tm["K"], tm["V"], lam, tm["dO"], dQ=tm["dQ"],
+                                                      dK=tm["dK"], dV=tm["dV"], workspace=ws), key="tmb")
+            tfb = _time(lambda: (binding.la_fwd_strided(tm["Q"], tm["K"], tm["V"], lam, O=tm["O"], workspace=ws),
+                                 binding.la_bwd_strided(tm["Q"], tm["K"], tm["V"], lam, tm["dO"], dQ=tm["dQ"],
+                                                        dK=tm["dK"], dV=tm["dV"], workspace=ws)), key="tmfb")
+            cont = [p for p in sweep if p["n"] == sn]
+            token_major.append({"B": sB, "n": sn, "fwd_ms": round(tf, 4), "bwd_ms": round(tb, 4),
+                                "fwd_bwd_ms": round(tfb, 4), "fwd_bwd_ms_min": leg_min["tmfb"],
+                                "tokens_per_s": round(TOKENS / (tfb * 1e-3), 1),
+                                "contiguous_fwd_bwd_ms": cont[0]["fwd_bwd_ms"] if cont else None})
 
         # ---- the sweep step captured once into a HIP graph and replayed (same calls, same kernels; only
         # the launches are issued by the graph instead of one by one from the host) -------------------------
@@ -568,6 +585,9 @@ def main():
         "fp32_path": fp32_path,
         "saved_states": saved_states,
         "graph_replay": graph_replay,
+        "token_major": {"workload": "la_fwd_strided + la_bwd_strided on [B, n, H, d] tensors (H=16, d=128, bf16, "
+                                    "65536 tokens), beside the contiguous [B, H, n, d] figure of the same point",
+                        "points": token_major} if token_major is not None else None,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
