@@ -457,3 +457,17 @@ def test_pseudo_random_shapes(i):
     ref = (oracle.c_recurrence_fwd(q, k, v, w.lambdas),) + oracle.c_recurrence_bwd(q, k, v, w.lambdas, g)
     got = _run_gpu(w, xs, lseg=lseg)
     _compare(w, got, ref, TOL[dtype], "case %d" % i)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
+def test_extreme_decay_rates(dtype, d):
+    """Decay rates from 1e-6 (every power beyond the first few underflows to zero) to 1 (no decay) in one
+    call, with and without forced segments: finite results, equal to the oracle within the tolerance."""
+    lam = [1e-6, 1e-2, 0.2, 1.0]
+    for n, lseg in ((300, None), (777, 128)):
+        w = synth.custom(2, 4, n, d, lam, seed=4242 + n + d, dtype=dtype)
+        xs = synth.draw(w)
+        q, k, v, g = _ref_inputs(xs, dtype)
+        ref = (oracle.c_recurrence_fwd(q, k, v, w.lambdas),) + oracle.c_recurrence_bwd(q, k, v, w.lambdas, g)
+        got = _run_gpu(w, xs, lseg=lseg)
+        _compare(w, got, ref, TOL[dtype], "%s d=%d n=%d lseg=%s" % (dtype, d, n, lseg))
