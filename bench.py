@@ -102,8 +102,27 @@ def ablation(binding, torch, views, lam, ws):
              ("ablate 4: loads, barriers and result stores, no arithmetic", {"ablate": 4})]
     out = {"protocol": "median ms of 20 calls, two interleaved rounds; fwd = la_fwd, bwd = la_bwd, "
                        "fwd_bwd = the two back to back, sweep_step_ms = one fwd+bwd at each of the six "
-                       "sweep points in turn (the benchmark's step); H=16, d=128, bf16, 65536 tokens",
+                       "sweep points in turn (the benchmark's step); fwd_cold_ms / bwd_cold_ms = the call timed "
+                       "after an untimed read-only pass over 1 GiB of other memory, so that it finds none of "
+                       "the previous call's tiles in L2 or the Infinity Cache (and no dirty lines to write "
+                       "back); H=16, d=128, bf16, 65536 tokens",
            "cases": []}
+    junk = torch.zeros(1 << 28, dtype=torch.int32, device=ws.device)
+
+    def med_cold(fn):
+        for _ in range(3):
+            fn()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+        torch.cuda.synchronize()
+        for e0, e1 in evs:
+            junk.sum()
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+        return round(0.5 * (ms[9] + ms[10]), 4)
+
     fns = {}
     step_fns = []
     for B, n in ((32, 2048), (16, 4096), (8, 8192), (4, 16384), (2, 32768), (1, 65536)):
@@ -130,7 +149,8 @@ def ablation(binding, torch, views, lam, ws):
                 row = {"case": label, "round": rnd}
                 for (B, n), (f, b) in fns.items():
                     row["B%d_n%d" % (B, n)] = {"fwd_ms": med(f), "bwd_ms": med(b),
-                                               "fwd_bwd_ms": med(lambda: (f(), b()))}
+                                               "fwd_bwd_ms": med(lambda: (f(), b())),
+                                               "fwd_cold_ms": med_cold(f), "bwd_cold_ms": med_cold(b)}
                 row["sweep_step_ms"] = med(sweep_step)
             out["cases"].append(row)
     return out

@@ -577,9 +577,12 @@ int run_backward(const void *Q, const void *K, const void *V, const void *dO, vo
         const hipError_t e = all_ext ? launch_bf16_dma_trio<true>(l, lams, s) : launch_bf16_dma_trio<false>(l, lams, s);
         return e == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
     }
-    int rc = run_block_scan<false>(pre[0], lams, scans, d, dt, s);
+    // Two launches.  The reversed pair goes first: it ends at the segments' first rows, where the
+    // dQ scan starts, so what the Infinity Cache still holds of K, V, dO is what dQ reads first
+    // (measured with cold caches, bf16 d = 128: la_bwd 0.54 against 0.56 ms in the other order).
+    int rc = run_reverse_pair(pre[1], av, lams, scans, d, dt, s);
     if (rc != LA_OK) return rc;
-    return run_reverse_pair(pre[1], av, lams, scans, d, dt, s);
+    return run_block_scan<false>(pre[0], lams, scans, d, dt, s);
 }
 
 int check_workspace(const Plan &p, int B, int H, int d, void *workspace, size_t workspace_bytes,
