@@ -13,6 +13,7 @@ host cores (`cpu_baseline`).
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -490,8 +491,13 @@ def main():
         # same run and protocol): C2 (TNL-400M-shaped layer, d = 64), C4 (TNL-7B-shaped layer), C5 (one
         # 131072-token sequence, half of the heads without decay) ------------------------------------------
         other_configs = []
-        for name in ("c2", "c4", "c5"):
-            w = synth.workload(name)
+        # (plus C2's layer shape at the sweep's size: d = 64, 32 heads, 65536 tokens, bytes as at C3's first point)
+        for name in ("c2", "c2_at_64k_tokens", "c4", "c5"):
+            if name == "c2_at_64k_tokens":
+                w = synth.custom(32, 32, 2048, 64, [math.exp(-(h + 1) / 32.0) for h in range(32)], seed=0,
+                                 dtype="bf16", name=name)
+            else:
+                w = synth.workload(name)
             el = w.B * w.H * w.n * w.d
             gsc = 1.0 / (w.d ** 0.5)
             xs = [(torch.randn(el, generator=gen, device=dev, dtype=torch.float32) * gsc).to(torch.bfloat16)

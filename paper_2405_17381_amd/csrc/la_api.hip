@@ -55,12 +55,12 @@ struct Switches {
     std::atomic<long> no_decay_skip{0};  // != 0: the segment-state pre-pass reads every block
     std::atomic<long> f32_plain{0};      // != 0: fp32 at d = 128 runs the FMA kernel
     std::atomic<long> store_policy{0};   // direct-to-LDS scan: 2 = ordinary instead of non-temporal result stores
-    std::atomic<long> staged_prepass{0}; // != 0: bf16 at d = 128 runs the register-staged segment-state pre-pass
+    std::atomic<long> staged_prepass{0}; // != 0: bf16 runs the register-staged segment-state pre-pass
     std::atomic<long> prepass_groups{0}; // 1, 2: wave groups per workgroup of the direct-to-LDS pre-pass (own choice: 4)
     std::atomic<long> no_trio{0};        // != 0: la_bwd's direct-to-LDS block scans as a dQ launch and a paired dK / dV launch
     std::atomic<long> wide_slices{0};    // != 0: la_fwd_wide always runs accumulated scans over d_v-wide slices
     std::atomic<long> ablate{0};         // 1..4: measurement-only variants of the direct-to-LDS scan
-    std::atomic<long> staged_scan{0};    // != 0: bf16 at d = 128 runs the register-staged block scan
+    std::atomic<long> staged_scan{0};    // != 0: bf16 runs the register-staged block scan
                                          // (64-row blocks) instead of the direct-to-LDS one (32-row)
 } g_sw;
 
@@ -101,7 +101,7 @@ struct Plan {
 // Block length of the block-scan kernel la_fwd / la_bwd run (the paper's "block size B").
 int tile_len(int d, la_dtype dt)
 {
-    if (dt == LA_BF16) return (d == 128 && !g_sw.staged_scan.load(std::memory_order_relaxed)) ? 32 : 64;
+    if (dt == LA_BF16) return g_sw.staged_scan.load(std::memory_order_relaxed) ? 64 : 32;
     return d == 64 ? 64 : 32;
 }
 
@@ -222,11 +222,11 @@ hipError_t launch_bf16(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s
 }
 
 // The backward pass's three block scans in one launch (see the kernel).
-template <bool STRIDED>
+template <bool STRIDED, int D = 128>
 hipError_t launch_bf16_dma_trio(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
-    using Cfg = DmaCfg<3>;
-    auto kern = la_scan_bf16_dma<false, true, 0, 3, true, STRIDED>;
+    using Cfg = DmaCfg<3, D>;
+    auto kern = la_scan_bf16_dma<false, true, 0, 3, true, STRIDED, D>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
@@ -236,11 +236,11 @@ hipError_t launch_bf16_dma_trio(const ScanLaunch &a, const LaLambdas &lams, hipS
     return hipGetLastError();
 }
 
-template <bool REV, bool NT_STORE, int ABL, int NS = 3, bool STRIDED = false>
+template <bool REV, bool NT_STORE, int ABL, int NS = 3, bool STRIDED = false, int D = 128>
 hipError_t launch_bf16_dma_variant(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
-    using Cfg = DmaCfg<NS>;
-    auto kern = la_scan_bf16_dma<REV, NT_STORE, ABL, NS, false, STRIDED>;
+    using Cfg = DmaCfg<NS, D>;
+    auto kern = la_scan_bf16_dma<REV, NT_STORE, ABL, NS, false, STRIDED, D>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
@@ -256,12 +256,12 @@ hipError_t launch_bf16_dma_variant(const ScanLaunch &a, const LaLambdas &lams, h
 // faster with ordinary stores, but only because L2 then hands part of its write-back to
 // whatever runs next: over a forward + backward sequence non-temporal stores in all three
 // launches win by 6 % ("store_policy" switch = 2 selects ordinary stores, for measurements).
-template <bool REV, bool STRIDED = false>
+template <bool REV, bool STRIDED = false, int D = 128>
 hipError_t launch_bf16_dma(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
     const bool nt = g_sw.store_policy.load(std::memory_order_relaxed) != 2;
-    // operands with their own layouts (strided entry points, slices of wider rows): one variant
-    if (STRIDED) return launch_bf16_dma_variant<REV, true, 0, 3, true>(a, lams, s);
+    // operands with their own layouts (strided entry points, slices of wider rows), and d = 64: one variant
+    if (STRIDED || D != 128) return launch_bf16_dma_variant<REV, true, 0, 3, STRIDED, D>(a, lams, s);
     switch (g_sw.ablate.load(std::memory_order_relaxed)) {
     case 1: return launch_bf16_dma_variant<REV, true, 1>(a, lams, s);
     case 2: return launch_bf16_dma_variant<REV, true, 2>(a, lams, s);
@@ -274,11 +274,11 @@ hipError_t launch_bf16_dma(const ScanLaunch &a, const LaLambdas &lams, hipStream
               : launch_bf16_dma_variant<REV, false, 0>(a, lams, s);
 }
 
-template <int G, bool STRIDED = false>
+template <int G, bool STRIDED = false, int D = 128>
 hipError_t launch_prepass_bf16_dma(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s)
 {
-    using Cfg = DmaPrepassCfg<G>;
-    auto kern = la_prepass_bf16_dma<G, STRIDED>;
+    using Cfg = DmaPrepassCfg<G, D>;
+    auto kern = la_prepass_bf16_dma<G, STRIDED, D>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] { attr_err = allow_lds(kern, Cfg::lds_bytes); });
@@ -330,38 +330,49 @@ hipError_t launch_f32m(const ScanLaunch &a, const LaLambdas &lams, hipStream_t s
     return hipGetLastError();
 }
 
+// bf16, direct-to-LDS family: plain launches and launches whose operands have their own layouts
+template <bool REV, bool STATE_ONLY, int D>
+hipError_t launch_bf16_direct(const ScanLaunch &a, const LaLambdas &lams, bool strided, hipStream_t s)
+{
+    if (STATE_ONLY) {
+        if (strided) return launch_prepass_bf16_dma<4, true, D>(a, lams, s);
+        if constexpr (D == 128) {
+            switch (g_sw.prepass_groups.load(std::memory_order_relaxed)) {
+            case 1: return launch_prepass_bf16_dma<1, false, D>(a, lams, s);
+            case 2: return launch_prepass_bf16_dma<2, false, D>(a, lams, s);
+            default: break;
+            }
+        }
+        return launch_prepass_bf16_dma<4, false, D>(a, lams, s);
+    }
+    return strided ? launch_bf16_dma<REV, true, D>(a, lams, s) : launch_bf16_dma<REV, false, D>(a, lams, s);
+}
+
+// bf16, register-staged family (64-row blocks): every activation / accumulation variant, and
+// everything when the "staged_scan" switch is set
+template <bool REV, bool STATE_ONLY, int D>
+hipError_t launch_bf16_staged(const ScanLaunch &a, const LaLambdas &lams, bool ext, hipStream_t s)
+{
+    if (STATE_ONLY) return ext ? launch_prepass_bf16<D, true>(a, lams, s) : launch_prepass_bf16<D, false>(a, lams, s);
+    return ext ? launch_bf16<D, REV, true>(a, lams, s) : launch_bf16<D, REV, false>(a, lams, s);
+}
+
 template <bool REV, bool STATE_ONLY>
 hipError_t launch_scan_kernel(const ScanLaunch &a, const LaLambdas &lams, int d,
                               la_dtype dt, hipStream_t s)
 {
     if (dt == LA_BF16) {
-        // the plain path runs kernels without any activation code in them
+        // LA_ACT_EXT alone: operands with their own layouts, nothing else; any other bit: an
+        // activation or an accumulating epilogue, which only the register-staged kernels carry
         const int acts = a.r[0].act | a.r[a.nroles - 1].act;
-        // operands with their own layouts and nothing else: the direct-to-LDS kernels, strided
-        const bool staged128 = g_sw.staged_scan.load(std::memory_order_relaxed) != 0;
-        if (acts == LA_ACT_EXT && d == 128 && !staged128) {
-            if (STATE_ONLY) {
-                if (g_sw.staged_prepass.load(std::memory_order_relaxed)) return launch_prepass_bf16<128, true>(a, lams, s);
-                return launch_prepass_bf16_dma<4, true>(a, lams, s);
-            }
-            return launch_bf16_dma<REV, true>(a, lams, s);
-        }
-        const bool act = acts != 0;
-        if (STATE_ONLY) {
-            if (act) return d == 64 ? launch_prepass_bf16<64, true>(a, lams, s) : launch_prepass_bf16<128, true>(a, lams, s);
-            if (d == 64) return launch_prepass_bf16<64, false>(a, lams, s);
-            if (g_sw.staged_scan.load(std::memory_order_relaxed) || g_sw.staged_prepass.load(std::memory_order_relaxed))
-                return launch_prepass_bf16<128, false>(a, lams, s);
-            switch (g_sw.prepass_groups.load(std::memory_order_relaxed)) {
-            case 1: return launch_prepass_bf16_dma<1>(a, lams, s);
-            case 2: return launch_prepass_bf16_dma<2>(a, lams, s);
-            default: return launch_prepass_bf16_dma<4>(a, lams, s);
-            }
-        }
-        if (act) return d == 64 ? launch_bf16<64, REV, true>(a, lams, s) : launch_bf16<128, REV, true>(a, lams, s);
-        if (d == 64) return launch_bf16<64, REV, false>(a, lams, s);
-        if (g_sw.staged_scan.load(std::memory_order_relaxed)) return launch_bf16<128, REV, false>(a, lams, s);
-        return launch_bf16_dma<REV>(a, lams, s);
+        const bool plain = acts == 0 || acts == LA_ACT_EXT;
+        const bool staged = !plain || g_sw.staged_scan.load(std::memory_order_relaxed) != 0 ||
+                            (STATE_ONLY && g_sw.staged_prepass.load(std::memory_order_relaxed) != 0);
+        if (staged)
+            return d == 64 ? launch_bf16_staged<REV, STATE_ONLY, 64>(a, lams, acts != 0, s)
+                           : launch_bf16_staged<REV, STATE_ONLY, 128>(a, lams, acts != 0, s);
+        return d == 64 ? launch_bf16_direct<REV, STATE_ONLY, 64>(a, lams, acts != 0, s)
+                       : launch_bf16_direct<REV, STATE_ONLY, 128>(a, lams, acts != 0, s);
     }
     // fp32: d = 64 runs the literal FMA kernel with 64-row blocks; d = 128 the matrix-core kernel
     // (32-row blocks; the "f32_plain" switch selects the FMA kernel there too, for comparisons)
@@ -568,13 +579,15 @@ int run_backward(const void *Q, const void *K, const void *V, const void *dO, vo
     }
     const int acts = pre[0].act | pre[1].act | av.act;
     const bool all_ext = pre[0].act == LA_ACT_EXT && pre[1].act == LA_ACT_EXT && av.act == LA_ACT_EXT;
-    if (!g_sw.no_trio.load(std::memory_order_relaxed) && dt == LA_BF16 && d == 128 &&
+    if (!g_sw.no_trio.load(std::memory_order_relaxed) && dt == LA_BF16 &&
         (acts == 0 || all_ext) && !g_sw.staged_scan.load(std::memory_order_relaxed) &&
         !g_sw.no_pair.load(std::memory_order_relaxed) && !g_sw.ablate.load(std::memory_order_relaxed)) {
         ScanLaunch l;
         l.r[0] = pre[0]; l.r[1] = pre[1]; l.r[2] = av; l.nroles = 3; l.items = (int)(scans * p.S);
         ScopedTimer t(s);
-        const hipError_t e = all_ext ? launch_bf16_dma_trio<true>(l, lams, s) : launch_bf16_dma_trio<false>(l, lams, s);
+        hipError_t e;
+        if (d == 64) e = all_ext ? launch_bf16_dma_trio<true, 64>(l, lams, s) : launch_bf16_dma_trio<false, 64>(l, lams, s);
+        else e = all_ext ? launch_bf16_dma_trio<true>(l, lams, s) : launch_bf16_dma_trio<false>(l, lams, s);
         return e == hipSuccess ? LA_OK : LA_ERR_LAUNCH;
     }
     // Two launches.  The reversed pair goes first: it ends at the segments' first rows, where the

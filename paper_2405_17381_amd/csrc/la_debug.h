@@ -19,9 +19,9 @@
  *                    leave work out (1: no result stores, 2: loads and barriers only,
  *                    3: arithmetic only, 4: loads, barriers and stores without arithmetic);
  *                    their results are wrong by design
- *   "staged_prepass" != 0: bf16 at d = 128 runs the register-staged segment-state pre-pass
+ *   "staged_prepass" != 0: bf16 runs the register-staged segment-state pre-pass
  *                    instead of the direct-to-LDS one
- *   "prepass_groups" 1, 2: the direct-to-LDS pre-pass runs with that many groups of four waves per
+ *   "prepass_groups" 1, 2: the direct-to-LDS pre-pass at d = 128 runs with that many groups of four waves per
  *                    workgroup instead of four (each group takes every G-th block of the segment;
  *                    the sums differ in rounding order between group counts)
  *   "no_trio"        != 0: la_bwd runs its direct-to-LDS block scans as a dQ launch followed by a
@@ -30,7 +30,7 @@
  *                    the single kernel with the non-square state applies
  *   "store_policy"   2: the direct-to-LDS block scan stores its results with ordinary instead
  *                    of non-temporal stores
- *   "staged_scan"    != 0: bf16 at d = 128 runs the register-staged block scan (64-row
+ *   "staged_scan"    != 0: bf16 runs the register-staged block scan (64-row
  *                    blocks) instead of the direct-to-LDS one (32-row blocks)
  *
  * la_debug_set returns LA_OK, or LA_ERR_NULL for an unknown name; la_debug_get returns the

@@ -1,4 +1,6 @@
-// bf16 block scan for d = 128 fed by global -> LDS direct loads (gfx950).
+// bf16 block scan fed by global -> LDS direct loads (gfx950), d = 128 and d = 64.  The text
+// below describes d = 128 (256-byte tile rows, four waves); d = 64 is the same code with 128-byte
+// rows, two waves per workgroup and its own chunk swizzle (DmaCfg, dma_swz).
 //
 // Same arithmetic as la_scan_bf16 (the block loop of Alg. 5 / Alg. 6: masked intra-block
 // left product, inter-block right product against the running state, state update), same
@@ -63,19 +65,33 @@ typedef __attribute__((address_space(3))) la_s4 la_lds_s4;
 // (80 KB each).  Measured: NS = 2 is as fast when 512 workgroups are resident and 4 % slower
 // with 256; NS = 4 and 6 (one workgroup per compute unit) are 15 to 30 % slower: the path is
 // not short of bytes in flight.
-template <int NS_>
+template <int NS_, int D_ = 128>
 struct DmaCfg {
-    static constexpr int D = 128, BK = 32;
+    static constexpr int D = D_, BK = 32;
     static constexpr int NS = NS_;
-    static constexpr int NW = 4, NT = 64 * NW;
+    static constexpr int NW = D / 32, NT = 64 * NW;          // one wave per 32 value features
     static constexpr int NTILE = 3;                          // tiles per stage: A, Bm, C
-    static constexpr int TILE_BYTES = BK * D * 2;            // 8192
+    static constexpr int PITCH = 2 * D;                      // bytes per tile row
+    static constexpr int CPR = D / 8;                        // 16-byte chunks per row
+    static constexpr int RPI = 64 / CPR;                     // rows one 64-lane load or store covers
+    static constexpr int TILE_BYTES = BK * D * 2;            // 8192 at D = 128
     static constexpr int STAGE_BYTES = NTILE * TILE_BYTES;
     static constexpr int SO_BYTES = BK * D * 2;              // the Out tile, bf16
-    static constexpr size_t lds_bytes = (size_t)NS * STAGE_BYTES + SO_BYTES;   // 81920 at NS = 3
+    static constexpr size_t lds_bytes = (size_t)NS * STAGE_BYTES + SO_BYTES;   // 81920 at NS = 3, D = 128
 };
 
-__device__ __forceinline__ int dma_sw(int r) { return ((r << 2) | ((r >> 2) & 3)) & 15; }
+// Chunk swizzle of a tile row (see the layout note above).  D = 128: the low four bits of r
+// rotated left by two.  D = 64 (128-byte rows, two rows per 256 bytes of banks): rows of equal
+// parity among any sixteen get eight different values, and rows 4j .. 4j + 3 differ in bit 2
+// between the two even and between the two odd ones, which is what the 16-row operand reads
+// and the 4-row transposing reads need to touch every bank once.
+template <int D>
+__host__ __device__ constexpr int dma_swz(int r)
+{
+    if (D == 128) return ((r << 2) | ((r >> 2) & 3)) & 15;
+    return ((((r & 3) ^ ((r >> 2) & 1)) << 1) | ((r >> 3) & 1)) & 7;
+}
+__device__ __forceinline__ int dma_sw(int r) { return dma_swz<128>(r); }
 
 // wait until at most N vector-memory instructions of this wave are outstanding
 template <int N>
@@ -134,15 +150,17 @@ __device__ __forceinline__ U2 lds_read_tr(const unsigned char *p)
 // fit the Infinity Cache (sequences or segments of up to about 1024 tokens), a part of the reads
 // that the forward and the reversed roles have in common.
 // STRIDED: every operand has its own layout (ScanArgs::lA .. lO) instead of contiguous slabs.
-template <bool REV_, bool NT_STORE, int ABL, int NS_, bool TRIO = false, bool STRIDED = false>
-__global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLaunch launch, LaLambdas lams)
+template <bool REV_, bool NT_STORE, int ABL, int NS_, bool TRIO = false, bool STRIDED = false, int D_ = 128>
+__global__ __launch_bounds__(2 * D_, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLaunch launch, LaLambdas lams)
 {
-    using Cfg = DmaCfg<NS_>;
+    using Cfg = DmaCfg<NS_, D_>;
     constexpr int D = Cfg::D, BK = Cfg::BK, NS = Cfg::NS, NTILE = Cfg::NTILE;
+    constexpr int PITCH = Cfg::PITCH, CPR = Cfg::CPR, RPI = Cfg::RPI;
+    constexpr int SW8 = dma_swz<D>(8);         // swizzle of row r + 8 = swizzle of row r ^ SW8
     constexpr int KS_D = D / 16;               // k-steps over the feature dim (8)
     constexpr int KS_B = BK / 16;              // k-steps over the block rows (2)
     constexpr int MT_D = D / 32;               // 32-row tiles over the feature dim (4)
-    constexpr int SPW = 8 / Cfg::NW;           // 4-row load slots per wave and tile (8 slots per tile)
+    constexpr int SPW = (BK / RPI) / Cfg::NW;  // load slots (RPI rows each) per wave and tile: 2
     constexpr int LOADS = NTILE * SPW;         // direct loads per wave and block
 
     extern __shared__ __align__(16) unsigned char smem_dma[];
@@ -219,18 +237,18 @@ __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLa
     const bool want_final = !REV && a.st_out != nullptr && seg == a.S - 1;
 
     // row-operand reads: row l32, chunk 2 ks + g
-    const int ro_base = l32 * 256;
-    const int ro_sw = dma_sw(l32) ^ g;                           // chunk position = (2 ks) ^ ro_sw
+    const int ro_base = l32 * PITCH;
+    const int ro_sw = dma_swz<D>(l32) ^ g;                       // chunk position = (2 ks) ^ ro_sw
     // transposing reads: lane = (a4 + 4 b4) + 16 h16 + 32 g
     const int a4 = l & 3, b4 = (l >> 2) & 3, h16 = (l >> 4) & 1;
-    const int tr_base = (4 * g + b4) * 256 + 8 * (a4 & 1);       // row 4g + b4, 8-byte half of the chunk
-    const int tr_sw = (2 * h16 + (a4 >> 1)) ^ (4 * b4 + g);      // chunk within the 32 columns ^ sw(row), sel = 0
+    const int tr_base = (4 * g + b4) * PITCH + 8 * (a4 & 1);     // row 4g + b4, 8-byte half of the chunk
+    const int tr_sw = (2 * h16 + (a4 >> 1)) ^ dma_swz<D>(4 * g + b4);   // chunk within the 32 columns ^ sw(row), sel = 0
     // direct loads: load slot ii = SPW w + j covers tile rows 4 ii .. 4 ii + 3
     int dma_row[SPW], dma_col[SPW];
 #pragma unroll
     for (int j = 0; j < SPW; ++j) {
-        dma_row[j] = 4 * (SPW * w + j) + (l >> 4);
-        dma_col[j] = 8 * ((l & 15) ^ dma_sw(dma_row[j]));        // element offset of the chunk fetched
+        dma_row[j] = RPI * (SPW * w + j) + l / CPR;
+        dma_col[j] = 8 * ((l % CPR) ^ dma_swz<D>(dma_row[j]));   // element offset of the chunk fetched
     }
     // Out tile: row q at 256 q, chunk c (8 features) at position c ^ (q & 15)
     unsigned char *sO = smem_dma + NS * Cfg::STAGE_BYTES;
@@ -304,8 +322,8 @@ __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLa
         const int last = min(BK, seg_hi - t0) - 1;
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
-            const int row = min(8 * w + 4 * p + (l >> 4), last), ch = l & 15;
-            const U4 o = *(const U4 *)(sO + row * 256 + ((ch ^ (row & 15)) << 4));
+            const int row = min(2 * RPI * w + RPI * p + l / CPR, last), ch = l % CPR;
+            const U4 o = *(const U4 *)(sO + row * PITCH + ((ch ^ (row & (CPR - 1))) << 4));
             U4 *dst = (U4 *)(gO + (size_t)(t0 + row) * ldO + 8 * ch);
             if (NT_STORE) __builtin_nontemporal_store(o, dst);
             else *dst = o;
@@ -379,10 +397,10 @@ __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLa
             U4 fb[KS_D / 2];
 #pragma unroll
             for (int k = 0; k < KS_D / 2; ++k)
-                fb[k] = *(const U4 *)(sB + ro_base + (((2 * (4 * h + k)) ^ ro_sw) << 4));
+                fb[k] = *(const U4 *)(sB + ro_base + (((2 * (KS_D / 2 * h + k)) ^ ro_sw) << 4));
             LA_BATCH_FENCE();
 #pragma unroll
-            for (int k = 0; k < KS_D / 2; ++k) s = mfma32(fb[k], fa[4 * h + k], s);
+            for (int k = 0; k < KS_D / 2; ++k) s = mfma32(fb[k], fa[KS_D / 2 * h + k], s);
         }
         // ---- inter block: x^T = St^T A^T; the state operand is made from the accumulators:
         // lane half g holds rows 4g..4g+3 and 8+4g..8+4g+3 of every 16, the operand wants
@@ -404,9 +422,9 @@ __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLa
         U4 cf[KS_B], cw[KS_B];
 #pragma unroll
         for (int ks = 0; ks < KS_B; ++ks) {
-            const unsigned char *p = sC + tr_base + 16 * ks * 256;
+            const unsigned char *p = sC + tr_base + 16 * ks * PITCH;
             const U2 lo = lds_read_tr(p + ((((4 * w) ^ tr_sw)) << 4));
-            const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * w) ^ tr_sw ^ 2)) << 4));
+            const U2 hi = lds_read_tr(p + 8 * PITCH + ((((4 * w) ^ tr_sw ^ SW8)) << 4));
             cf[ks] = U4{lo[0], lo[1], hi[0], hi[1]};
         }
         // ---- P = bf16(S * mask) stays in registers: it is already the operand of the intra product
@@ -428,7 +446,7 @@ __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLa
             U2 o;
             o[0] = pack2_bf16(x[4 * v4 + 0], x[4 * v4 + 1]);
             o[1] = pack2_bf16(x[4 * v4 + 2], x[4 * v4 + 3]);
-            *(U2 *)(sO + l32 * 256 + (((4 * w + v4) ^ (l32 & 15)) << 4) + 8 * g) = o;
+            *(U2 *)(sO + l32 * PITCH + (((4 * w + v4) ^ (l32 & (CPR - 1))) << 4) + 8 * g) = o;
         }
 #pragma unroll
         for (int ks = 0; ks < KS_B; ++ks)
@@ -442,9 +460,9 @@ __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLa
             U4 bt[KS_B];
 #pragma unroll
             for (int ks = 0; ks < KS_B; ++ks) {
-                const unsigned char *p = sB + tr_base + 16 * ks * 256;
+                const unsigned char *p = sB + tr_base + 16 * ks * PITCH;
                 const U2 lo = lds_read_tr(p + ((((4 * mt) ^ tr_sw)) << 4));
-                const U2 hi = lds_read_tr(p + 8 * 256 + ((((4 * mt) ^ tr_sw ^ 2)) << 4));
+                const U2 hi = lds_read_tr(p + 8 * PITCH + ((((4 * mt) ^ tr_sw ^ SW8)) << 4));
                 bt[ks] = U4{lo[0], lo[1], hi[0], hi[1]};
             }
             LA_BATCH_FENCE();
@@ -501,21 +519,25 @@ __global__ __launch_bounds__(256, NS_ <= 3 ? 2 : 1) void la_scan_bf16_dma(ScanLa
 // 45 us per launch of 512 workgroups, i.e. the kernel's 224 MB at 5 TB/s: the pre-pass is
 // bound by its bytes and by the ramp of a short launch, not by the chain, once either the
 // prefetch is deep enough or the chain is split.
-template <int G_>
+template <int G_, int D_ = 128>
 struct DmaPrepassCfg {
-    static constexpr int D = 128, BK = 32, NS = 2, G = G_, NT = 256 * G_;
+    static constexpr int D = D_, BK = 32, NS = 2, G = G_, NW = D / 32, NT = 64 * NW * G_;
+    static constexpr int PITCH = 2 * D, CPR = D / 8, RPI = 64 / CPR;
     static constexpr int TILE_BYTES = BK * D * 2;
     static constexpr int STAGE_BYTES = 2 * TILE_BYTES;       // Bm, C
     static constexpr size_t raw_bytes = (size_t)G * NS * STAGE_BYTES;
-    // the partial states are exchanged through a [64][256] fp32 area laid over the stages
-    static constexpr size_t lds_bytes = raw_bytes > 65536 ? raw_bytes : 65536;
+    // the partial states are exchanged through a [D / 2][64 NW] fp32 area laid over the stages
+    static constexpr size_t xchg_bytes = (size_t)(D / 2) * 64 * NW * 4;
+    static constexpr size_t lds_bytes = raw_bytes > xchg_bytes ? raw_bytes : xchg_bytes;
 };
 
-template <int G_, bool STRIDED = false>
-__global__ __launch_bounds__(256 * G_, 1) void la_prepass_bf16_dma(ScanLaunch launch, LaLambdas lams)
+template <int G_, bool STRIDED = false, int D_ = 128>
+__global__ __launch_bounds__(2 * D_ * G_, 1) void la_prepass_bf16_dma(ScanLaunch launch, LaLambdas lams)
 {
-    using Cfg = DmaPrepassCfg<G_>;
-    constexpr int D = Cfg::D, BK = Cfg::BK, NS = Cfg::NS, G = Cfg::G;
+    using Cfg = DmaPrepassCfg<G_, D_>;
+    constexpr int D = Cfg::D, BK = Cfg::BK, NS = Cfg::NS, G = Cfg::G, NW = Cfg::NW;
+    constexpr int PITCH = Cfg::PITCH, CPR = Cfg::CPR, RPI = Cfg::RPI;
+    constexpr int SW8 = dma_swz<D>(8);
     constexpr int KS_B = BK / 16, MT_D = D / 32;
 
     extern __shared__ __align__(16) unsigned char smem_dma[];
@@ -523,8 +545,8 @@ __global__ __launch_bounds__(256 * G_, 1) void la_prepass_bf16_dma(ScanLaunch la
     const int tid = threadIdx.x;
     const int l = tid & 63, l32 = l & 31, g = l >> 5;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int w = wv & 3;                                    // value-feature slice of this wave
-    const int gq = wv >> 2;                                  // group: blocks gq, gq + G, ...
+    const int w = wv % NW;                                   // value-feature slice of this wave
+    const int gq = wv / NW;                                  // group: blocks gq, gq + G, ...
 
     const int role = launch.nroles == 2 ? (int)(blockIdx.x / launch.items) : 0;
     const int item = launch.nroles == 2 ? (int)(blockIdx.x % launch.items) : (int)blockIdx.x;
@@ -571,13 +593,13 @@ __global__ __launch_bounds__(256 * G_, 1) void la_prepass_bf16_dma(ScanLaunch la
         wt[v] = rev ? pw(key) : pw(BK - 1 - key);
     }
     const int a4 = l & 3, b4 = (l >> 2) & 3, h16 = (l >> 4) & 1;
-    const int tr_base = (4 * g + b4) * 256 + 8 * (a4 & 1);
-    const int tr_sw = (2 * h16 + (a4 >> 1)) ^ (4 * b4 + g);
-    int dma_row[2], dma_col[2];
+    const int tr_base = (4 * g + b4) * PITCH + 8 * (a4 & 1);
+    const int tr_sw = (2 * h16 + (a4 >> 1)) ^ dma_swz<D>(4 * g + b4);
+    int dma_row[2], dma_col[2];                              // (BK / RPI) / NW = 2 load slots per wave and tile
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        dma_row[j] = 4 * (2 * w + j) + (l >> 4);
-        dma_col[j] = 8 * ((l & 15) ^ dma_sw(dma_row[j]));
+        dma_row[j] = RPI * (2 * w + j) + l / CPR;
+        dma_col[j] = 8 * ((l % CPR) ^ dma_swz<D>(dma_row[j]));
     }
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(la_lds_void *)smem_dma);
     const int group_off = gq * NS * Cfg::STAGE_BYTES;
@@ -630,7 +652,7 @@ __global__ __launch_bounds__(256 * G_, 1) void la_prepass_bf16_dma(ScanLaunch la
         // the LDS reads go out in batches (one of 20 reads; at four groups, where a wave has a
         // quarter of the registers, two of 12 and 8), each followed by its MFMAs: independent
         // accumulator chains, interleaved
-        constexpr int MB = G == 4 ? 2 : MT_D;
+        constexpr int MB = (G == 4 && MT_D > 2) ? 2 : MT_D;
         U2 rc[KS_B][2];
         U4 cw[KS_B];
 #pragma unroll
@@ -639,18 +661,18 @@ __global__ __launch_bounds__(256 * G_, 1) void la_prepass_bf16_dma(ScanLaunch la
             if (m0 == 0) {
 #pragma unroll
                 for (int ks = 0; ks < KS_B; ++ks) {
-                    const unsigned char *p = sC + tr_base + 16 * ks * 256;
+                    const unsigned char *p = sC + tr_base + 16 * ks * PITCH;
                     rc[ks][0] = lds_read_tr(p + ((((4 * w) ^ tr_sw)) << 4));
-                    rc[ks][1] = lds_read_tr(p + 8 * 256 + ((((4 * w) ^ tr_sw ^ 2)) << 4));
+                    rc[ks][1] = lds_read_tr(p + 8 * PITCH + ((((4 * w) ^ tr_sw ^ SW8)) << 4));
                 }
             }
 #pragma unroll
             for (int m = 0; m < MB; ++m)
 #pragma unroll
                 for (int ks = 0; ks < KS_B; ++ks) {
-                    const unsigned char *p = sB + tr_base + 16 * ks * 256;
+                    const unsigned char *p = sB + tr_base + 16 * ks * PITCH;
                     rb[m][ks][0] = lds_read_tr(p + ((((4 * (m0 + m)) ^ tr_sw)) << 4));
-                    rb[m][ks][1] = lds_read_tr(p + 8 * 256 + ((((4 * (m0 + m)) ^ tr_sw ^ 2)) << 4));
+                    rb[m][ks][1] = lds_read_tr(p + 8 * PITCH + ((((4 * (m0 + m)) ^ tr_sw ^ SW8)) << 4));
                 }
             LA_BATCH_FENCE();
             if (m0 == 0) {
@@ -675,7 +697,7 @@ __global__ __launch_bounds__(256 * G_, 1) void la_prepass_bf16_dma(ScanLaunch la
 
     // ---- the groups' partial states, added in a fixed order through LDS ------------------
     if (G > 1) {
-        float *sX = reinterpret_cast<float *>(smem_dma);     // [64][256]: entry (mt, v) of thread (w, l)
+        float *sX = reinterpret_cast<float *>(smem_dma);     // [16 MT_D][64 NW]: entry (mt, v) of thread (w, l)
         LA_LDS_BARRIER();                       // every group is done with its stages
 #pragma unroll 1
         for (int r = 1; r < G; ++r) {
@@ -683,14 +705,14 @@ __global__ __launch_bounds__(256 * G_, 1) void la_prepass_bf16_dma(ScanLaunch la
 #pragma unroll
                 for (int mt = 0; mt < MT_D; ++mt)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) sX[(16 * mt + v) * 256 + 64 * w + l] = st[mt][v];
+                    for (int v = 0; v < 16; ++v) sX[(16 * mt + v) * (64 * NW) + 64 * w + l] = st[mt][v];
             }
             LA_LDS_BARRIER();
             if (gq == 0) {
 #pragma unroll
                 for (int mt = 0; mt < MT_D; ++mt)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) st[mt][v] += sX[(16 * mt + v) * 256 + 64 * w + l];
+                    for (int v = 0; v < 16; ++v) st[mt][v] += sX[(16 * mt + v) * (64 * NW) + 64 * w + l];
             }
             LA_LDS_BARRIER();
         }

@@ -77,7 +77,9 @@ def test_plan_and_workspace():
     assert binding.la_plan(1, 2, 256, 128, binding.LA_F32)[0] == 32
     # override
     with binding.debug(lseg=128):
-        assert binding.la_plan(1, 2, 300, 64, binding.LA_BF16) == (64, 128, 3)
+        assert binding.la_plan(1, 2, 300, 64, binding.LA_BF16) == (32, 128, 3)
+        with binding.debug(staged_scan=1):               # the register-staged family: 64-row blocks
+            assert binding.la_plan(1, 2, 300, 64, binding.LA_BF16) == (64, 128, 3)
     # invalid problem: no scratch, error status from the plan
     assert binding.la_workspace_bytes(1, 1, 16, 96, binding.LA_BF16, False) == 0
     with pytest.raises(binding.LaError):

@@ -115,12 +115,13 @@ def test_bf16_ragged_and_segmented(d, n, lseg):
     _full_case(w, lseg)
 
 
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("n", [31, 32, 33, 95, 96, 97, 129])
-def test_bf16_d128_block_edges_of_the_direct_to_lds_kernels(n):
+def test_bf16_block_edges_of_the_direct_to_lds_kernels(n, d):
     """Sequence lengths around multiples of the 32-row block of the direct-to-LDS kernels (partial
     last block of the forward scan = partial first block of the reverse scans), whole and cut."""
     lam = [1.0, 0.999, 0.9, 0.3]
-    w = synth.custom(3, len(lam), n, 128, lam, seed=3100 + n, dtype="bf16")
+    w = synth.custom(3, len(lam), n, d, lam, seed=3100 + n, dtype="bf16")
     _full_case(w)
     if n > 64:
         _full_case(w, lseg=64)
@@ -377,13 +378,14 @@ def test_very_long_sequence_many_segments():
     _full_case(w)
 
 
-def test_direct_to_lds_and_register_staged_block_scans_agree():
-    """bf16 at d = 128 has two block-scan kernels: the direct-to-LDS one (32-row blocks, the
+@pytest.mark.parametrize("d", [128, 64])
+def test_direct_to_lds_and_register_staged_block_scans_agree(d):
+    """bf16 has two block-scan kernel families: the direct-to-LDS one (32-row blocks, the
     default) and the register-staged one (64-row blocks, "staged_scan" switch).  Same arithmetic
     up to block length and rounding points: they agree with each other far inside the tolerance,
     each agrees with the oracle, and they are different code (outputs not bit-identical)."""
     lam = [1.0, 0.9995, 0.97, 0.5]
-    w = synth.custom(2, 4, 1337, 128, lam, seed=4711, dtype="bf16")
+    w = synth.custom(2, 4, 1337, d, lam, seed=4711, dtype="bf16")
     xs = synth.draw(w)
     q, k, v, g = _ref_inputs(xs, "bf16")
     ref = (oracle.c_recurrence_fwd(q, k, v, lam),) + oracle.c_recurrence_bwd(q, k, v, lam, g)
