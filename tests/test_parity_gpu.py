@@ -306,6 +306,15 @@ def test_c3_sweep_point_every_scan(n):
     _full_size_case(synth.workload("c3_%d" % n), chunk=16)
 
 
+def test_c2_layer_at_65536_tokens_every_scan():
+    """C2's layer shape (d = 64, strong decay) at the size the benchmark's `c2_at_64k_tokens` entry times:
+    32 x 32 scans of 2048 tokens, unsegmented, every scan against the oracle."""
+    import math
+    w = synth.custom(32, 32, 2048, 64, [math.exp(-(h + 1) / 32.0) for h in range(32)], seed=20240599,
+                     dtype="bf16", name="c2_at_64k_tokens")
+    _full_size_case(w, chunk=32)
+
+
 def test_c4_silu_features_every_scan():
     _full_size_case(synth.workload("c4"), chunk=16)
 
