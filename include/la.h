@@ -112,8 +112,9 @@ int la_fwd(const void *Q, const void *K, const void *V,
  * tensors and `hip_stream` belong to must be the current device.
  * A problem for which la_workspace_bytes(B, H, n, d, dt, 0) exceeds
  * LA_STATIC_SCRATCH_BYTES is refused with LA_ERR_TOO_LARGE and nothing is enqueued.
- * (The planner cuts a problem into fewer than 768 (scan, segment) pieces of d*d*4 bytes
- * each, so 64 MiB holds every plan it makes by itself, whatever B, H and n.)
+ * (The planner cuts a problem into fewer than 768 (scan, segment) pieces of 64 KB at
+ * d = 128 and fewer than 1280 of 16 KB at d = 64, so 64 MiB holds every plan it makes by
+ * itself, whatever B, H and n.)
  * All calls on one GPU share that GPU's buffer: calls that may overlap in time on one GPU
  * (different streams, different threads) race and must be serialised by the caller.
  * Nothing in the buffer needs clearing between calls.

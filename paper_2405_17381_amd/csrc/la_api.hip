@@ -89,7 +89,10 @@ constexpr int kComputeUnits = 256;
 // Measured on the 64K-token sweep: one workgroup per unit without the segment-
 // state pre-pass beats two per unit with it, and 2048-token segments are best
 // among 512..8192.
+// bf16 at d = 64 runs two-wave workgroups, four to a unit: measured at 64 and 32 scans of 32K and
+// 64K tokens, 2048-token segments (1024 workgroups) beat 4096-token ones (512) by 3 to 5 %.
 constexpr int kTargetWorkgroups = 2 * kComputeUnits;
+constexpr int kTargetWorkgroupsBf16D64 = 4 * kComputeUnits;
 constexpr int kMinSegmentTokens = 512;
 
 struct Plan {
@@ -119,7 +122,9 @@ Plan make_plan(int B, int H, int n, int d, la_dtype dt)
     const long scans = (long)B * H;
     int L = round_up(n, gran);
     if (scans < kComputeUnits) {
-        const long want = (kTargetWorkgroups + scans - 1) / scans;   // segments wanted per scan
+        const bool small_wgs = dt == LA_BF16 && d == 64 && !g_sw.staged_scan.load(std::memory_order_relaxed);
+        const long target = small_wgs ? kTargetWorkgroupsBf16D64 : kTargetWorkgroups;
+        const long want = (target + scans - 1) / scans;              // segments wanted per scan
         long l = (n + want - 1) / want;
         if (l < kMinSegmentTokens) l = kMinSegmentTokens;
         l = round_up((int)l, gran);
