@@ -29,7 +29,6 @@ __global__ __launch_bounds__(256, 1) void la_scan_bf16_dma_wide(ScanLaunch launc
 {
     using Cfg = DmaWideCfg;
     constexpr int DK = Cfg::DK, DV = Cfg::DV, BK = Cfg::BK, NS = Cfg::NS, PF = NS - 1;
-    constexpr int KS_D = DK / 16;              // k-steps over the query / key features (16)
     constexpr int KS_B = BK / 16;              // k-steps over the block rows (2)
     constexpr int MT_D = DK / 32;              // 32-row tiles of the state (8)
     constexpr int LOADS = 4 + 4 + 2;           // direct loads per wave and block (A, Bm, C)
