@@ -482,3 +482,32 @@ def test_extreme_decay_rates(dtype, d):
         ref = (oracle.c_recurrence_fwd(q, k, v, w.lambdas),) + oracle.c_recurrence_bwd(q, k, v, w.lambdas, g)
         got = _run_gpu(w, xs, lseg=lseg)
         _compare(w, got, ref, TOL[dtype], "%s d=%d n=%d lseg=%s" % (dtype, d, n, lseg))
+
+
+def test_tensors_beyond_2_to_the_31_elements():
+    """64 heads x 270 000 tokens x 128 features = 2.2e9 elements (4.4 GB) per tensor: element offsets
+    of the later heads do not fit 32 bits.  Inputs drawn on the device; the first head, the head
+    that straddles 2^31 elements and the last head are compared with the oracle over their whole
+    length, O and all gradients; every output is checked to be fully written."""
+    B, H, n, d = 1, 64, 270_000, 128
+    assert H * n * d > 2 ** 31
+    lam = [float(np.float32(0.9 + 0.0999 * h / (H - 1))) for h in range(H)]
+    gen = torch.Generator(device="cuda").manual_seed(777)
+    ins = [(torch.randn((B, H, n, d), generator=gen, device="cuda", dtype=torch.bfloat16) * s)
+           for s in (0.088, 0.088, 0.088, 1.0)]
+    outs = [torch.full((B, H, n, d), float("nan"), device="cuda", dtype=torch.bfloat16) for _ in range(4)]
+    binding.la_fwd(ins[0], ins[1], ins[2], lam, O=outs[0])
+    binding.la_bwd(ins[0], ins[1], ins[2], lam, ins[3], dQ=outs[1], dK=outs[2], dV=outs[3])
+    torch.cuda.synchronize()
+    _say("plan (tile, L, S) = %s" % (binding.la_plan(B, H, n, d, binding.LA_BF16),))
+    for nm, t in zip(("O", "dQ", "dK", "dV"), outs):
+        for h0 in range(0, H, 8):                        # in pieces: keeps the fp32 temporaries small
+            assert not torch.isnan(t[:, h0:h0 + 8].float()).any(), (nm, "unwritten", h0)
+    straddle = (2 ** 31) // (n * d)
+    for h in (0, straddle, H - 1):
+        q, k, v, g = [x[:, h:h + 1].to(torch.float64).cpu().numpy() for x in ins]
+        ref = (oracle.c_recurrence_fwd(q, k, v, [lam[h]]),) + oracle.c_recurrence_bwd(q, k, v, [lam[h]], g)
+        for nm, t, r in zip(("O", "dQ", "dK", "dV"), outs, ref):
+            err = oracle.rel_max_err(t[:, h:h + 1].to(torch.float64).cpu().numpy(), r)
+            _say("  head %d %s: rel err %.3e" % (h, nm, err))
+            assert err <= TOL["bf16"], (h, nm, err)
